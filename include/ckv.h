@@ -1,0 +1,175 @@
+/*
+ * ckv.h -- C ABI of the CompilerKV prefill-end retention step for AMD MI355X (gfx950).
+ *
+ * The library implements the online pass of CompilerKV (paper Sec. 4, Alg. 1) for ONE layer per call
+ * sequence, cut into four asynchronous calls that are queued back-to-back on one HIP stream:
+ *
+ *   ckv_window_scores -> ckv_apply_tables -> ckv_select_topk -> ckv_compact_kv
+ *
+ * Notation (paper Sec. 3-4): T = prompt length (keys/values cached at the end of prefill, the
+ * observation window included), W = |Omega| = observation window (the last W query positions),
+ * P = T - W = prefix length that competes for the budget, Hq / Hkv = query / key-value heads,
+ * G = Hq / Hkv (query heads [g*G, (g+1)*G) share KV head g), d = head_dim, B = token budget per KV
+ * head (the W window slots included), B_tot = B * Hkv = the layer's total.
+ *
+ * Conventions that hold for every entry point unless a comment says otherwise:
+ *   - every data pointer is a DEVICE pointer owned by the caller; the library never allocates, frees
+ *     or keeps device memory, keeps no state between calls and never synchronises;
+ *   - `params` is a HOST pointer, read during the call only;
+ *   - every call only enqueues work on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and returns; outputs are valid once the stream reaches that point;
+ *   - inputs are never written; outputs must not alias inputs or each other;
+ *   - arguments are validated on the host BEFORE anything is launched: on any error nothing has
+ *     been enqueued and the status says why (ckv_status_string gives text);
+ *   - tensors are dense row-major in the order written in their comment, except Q/K/V which carry
+ *     explicit (batch, head, token) strides in ELEMENTS with the head_dim axis contiguous.
+ */
+#ifndef CKV_H_
+#define CKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CKV_OK = 0,
+  CKV_EINVAL = 1,       /* a null pointer, a size or a flag outside the documented domain          */
+  CKV_EUNSUPPORTED = 2, /* valid, but not built (e.g. head_dim other than 64 / 128 / 256)          */
+  CKV_EWORKSPACE = 3,   /* workspace missing, misaligned (256 B) or smaller than ckv_workspace_bytes */
+  CKV_EHIP = 4          /* the HIP runtime refused a launch; see hipGetLastError                   */
+} ckv_status;
+
+typedef enum { CKV_F32 = 0, CKV_BF16 = 1 } ckv_dtype;              /* element type of Q, K, V      */
+typedef enum { CKV_POOL_NONE = 0, CKV_POOL_AVG = 1, CKV_POOL_MAX = 2 } ckv_pool;
+
+/* flags */
+enum {
+  CKV_FLAG_VALUE_NORM = 1u /* multiply the window mass by the value-norm ratio rho (paper Eq. 4)   */
+};
+
+/* Problem description shared by all calls. Plain data; the caller may reuse or free it after a call. */
+typedef struct {
+  int32_t batch;          /* Bz >= 1                                                               */
+  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                                          */
+  int32_t n_kv_heads;     /* Hkv >= 1                                                              */
+  int32_t head_dim;       /* d: 64, 128 or 256                                                     */
+  int32_t seq_len;        /* T, window included; 1 <= W <= T                                       */
+  int32_t window;         /* W                                                                     */
+  int32_t layer;          /* row of the compiled tables used by this call, 0 <= layer < n_layers   */
+  int32_t n_layers;       /* rows in w_head / head_share / t_gate                                  */
+  int32_t dtype;          /* ckv_dtype of q_win, k, v, k_out, v_out                                */
+  float softmax_scale;    /* logit scale; 0 selects 1/sqrt(head_dim) (paper Sec. 3)                */
+  int64_t q_stride[3];    /* element strides of q_win over (batch, q head, window row)             */
+  int64_t k_stride[3];    /* element strides of k over (batch, kv head, token)                     */
+  int64_t v_stride[3];    /* element strides of v over (batch, kv head, token)                     */
+  int32_t pool;           /* ckv_pool: 1-D pooling of the window mass along the token axis         */
+  int32_t pool_kernel;    /* odd, 1..63; ignored for CKV_POOL_NONE                                 */
+  int32_t budget_per_kv_head; /* B, W <= B (window slots included)                                 */
+  int32_t cap;            /* rows per (batch, kv head) in idx / k_out / v_out;
+                             cap >= min(T, B_tot - (Hkv-1)*W), the largest budget one head can get */
+  uint32_t flags;         /* CKV_FLAG_*                                                            */
+} ckv_params;
+
+/* Bytes of scratch that ckv_window_scores and ckv_select_topk need for `params` (the larger of the
+ * two; the calls of one layer may share one buffer because they run in stream order).
+ * Returns 0 if `params` is NULL or invalid. The buffer must be 256-byte aligned. */
+size_t ckv_workspace_bytes(const ckv_params *params);
+
+/*
+ * Observation-window scan (paper Sec. 3 attention definition, Eq. 3 "the O(LHTW) scan", Eq. 4's
+ * alpha_t taken per query head, Alg. 1 step (A)).
+ *
+ * For every batch element b, query head h and key position t in [0, T):
+ *     z[j,t]      = softmax_scale * <q_win[b,h,j,:], k[b,g(h),t,:]>            j in [0, W)
+ *     A[j,t]      = exp(z[j,t] - LSE_j),  LSE_j = log sum_{t' <= P+j} exp z[j,t']   (causal: window
+ *                   row j sits at absolute position P+j and sees keys t' <= P+j; A[j,t] = 0 beyond)
+ *     scores[b,h,t] = (T / W) * sum_j A[j,t]
+ * so that sum_t scores[b,h,t] = T (mean one, the paper's scale normalisation).
+ *
+ *   q_win        in   [Bz,Hq,W,d]  via q_stride; the last W query rows of the prompt
+ *   k            in   [Bz,Hkv,T,d] via k_stride
+ *   v            in   [Bz,Hkv,T,d] via v_stride; read only with CKV_FLAG_VALUE_NORM, else may be NULL
+ *   lse          in   optional [Bz,Hq,W] fp32 natural-log LSE_j as defined above (for callers whose
+ *                     prefill attention kernel already produced it); NULL = computed here with one
+ *                     extra pass over K
+ *   scores       out  [Bz,Hq,T] fp32
+ *   vnorm_ratio  out  [Bz,Hkv,T] fp32, rho[t] = ||v_t||_2 / (mean_{t'<T} ||v_t'||_2 + 1e-6)
+ *                     (paper Eq. 4, Alg. 1 Stage 1); required with CKV_FLAG_VALUE_NORM, else ignored
+ *   workspace         ckv_workspace_bytes(params) bytes, contents undefined before and after
+ * Accumulation is fp32 (bf16 inputs go through bf16 MFMA with fp32 accumulators).
+ */
+ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const void *k,
+                             const void *v, const float *lse, float *scores, float *vnorm_ratio,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Pooling, compiled-table lookups and budgets (paper Eq. 6 weighted max over heads, Sec. 4.3 gate
+ * lookup, Alg. 1 Stages 2-3 up to the threshold; the 1-D pooling and the per-head budget split are
+ * the build's workload definition, not the paper's).
+ *
+ * For every b, kv head g and prefix position t in [0, P):
+ *     c[h,t]  = pool_k(scores[b,h,0:P])[t]   centred, stride 1, same length; AVG divides by
+ *               pool_kernel with zeros outside [0,P); MAX ignores positions outside [0,P)
+ *     u[h,t]  = c[h,t] * vnorm_ratio[b,g,t]  (with CKV_FLAG_VALUE_NORM, else u = c)
+ *     utility[b,g,t] = max_{h in group g} fp32(w_head[layer,h] * u[h,t])
+ * and
+ *     tau[b]  = t_gate[layer, risk_bins[b,0], risk_bins[b,1]]       (0 if t_gate is NULL: gate off)
+ *     budget[b,g]: NULL head_share => B. Else b_g = floor(head_share[layer,g] * B_tot) evaluated in
+ *               fp64, clamped to [W, T]; while sum_g b_g > B_tot the largest b_g that is > W (lowest
+ *               g on ties) is decremented by one.
+ *
+ *   scores       in   [Bz,Hq,T] fp32 (from ckv_window_scores)
+ *   vnorm_ratio  in   [Bz,Hkv,T] fp32, required with CKV_FLAG_VALUE_NORM
+ *   w_head       in   [n_layers,Hq] fp32, finite and > 0 (paper grid: [0.8,1.5])
+ *   head_share   in   [n_layers,Hkv] fp32 >= 0, or NULL
+ *   t_gate       in   [n_layers,n_ent,n_ppl] fp32 >= 0 (paper grid: 20 x 4, values in [0.8,1.0]), or NULL
+ *   risk_bins    in   [Bz,2] int32 (b_ent, b_ppl), required with t_gate; out-of-range bins are
+ *                     clamped into the table on the device (they cannot be checked on the host)
+ *   utility      out  [Bz,Hkv,P] fp32
+ *   budget       out  [Bz,Hkv] int32
+ *   tau          out  [Bz] fp32
+ */
+ckv_status ckv_apply_tables(const ckv_params *params, const float *scores, const float *vnorm_ratio,
+                            const float *w_head, const float *head_share, const float *t_gate,
+                            int32_t n_ent, int32_t n_ppl, const int32_t *risk_bins, float *utility,
+                            int32_t *budget, float *tau, void *hip_stream);
+
+/*
+ * Elastic candidate pool with budget clamp (paper Eq. 8, Alg. 1 Select), per (b, kv head g):
+ *     cand = { t < P : utility[b,g,t] >= tau[b] },  kp = budget[b,g] - W
+ *     Sp   = cand                                         if |cand| <= kp
+ *          = the kp members of cand that come first under (utility descending, t ascending) otherwise
+ *     idx[b,g,:] = Sp in ascending t, then the window P..T-1;   count[b,g] = |Sp| + W
+ * Utilities must be non-negative and not NaN (they are sums of softmax weights times positive
+ * weights); the order of equal utilities is by position, so the result is unique.
+ *
+ *   utility  in   [Bz,Hkv,P] fp32      budget in [Bz,Hkv] int32 (values are clamped to [W, min(cap,T)]
+ *   tau      in   [Bz] fp32                       on the device)
+ *   idx      out  [Bz,Hkv,cap] int32; entries at and beyond count[b,g] are not written
+ *   count    out  [Bz,Hkv] int32
+ */
+ckv_status ckv_select_topk(const ckv_params *params, const float *utility, const int32_t *budget,
+                           const float *tau, int32_t *idx, int32_t *count, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Token-axis gather (paper Sec. 3 "K~ = K[S], V~ = V[S]", Alg. 1 Gather_tok): for r < count[b,g]
+ *     k_out[b,g,r,:] = k[b,g,idx[b,g,r],:]    v_out[b,g,r,:] = v[b,g,idx[b,g,r],:]     (bit copies)
+ *
+ *   k, v          in   via k_stride / v_stride
+ *   idx, count    in   from ckv_select_topk; indices outside [0,T) are skipped on the device
+ *   k_out, v_out  out  [Bz,Hkv,cap,d] dense, same dtype; rows at and beyond count are not written
+ */
+ckv_status ckv_compact_kv(const ckv_params *params, const void *k, const void *v, const int32_t *idx,
+                          const int32_t *count, void *k_out, void *v_out, void *hip_stream);
+
+/* Static text for a status code; never NULL. */
+const char *ckv_status_string(ckv_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKV_H_ */
