@@ -1,0 +1,193 @@
+// C-ABI entry points of libckv: argument validation on the host, then kernel launches.
+// Nothing here allocates or synchronises; every entry point either enqueues all of its kernels on
+// the caller's stream or returns an error before the first launch.
+#include <math.h>
+
+#include "ckv_internal.h"
+
+namespace ckv {
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+ckv_status validate(const ckv_params *p) {
+  if (!p) return CKV_EINVAL;
+  if (p->batch < 1 || p->n_kv_heads < 1 || p->n_q_heads < 1) return CKV_EINVAL;
+  if (p->n_q_heads % p->n_kv_heads) return CKV_EINVAL;
+  if (p->seq_len < 1 || p->window < 1 || p->window > p->seq_len) return CKV_EINVAL;
+  if (p->n_layers < 1 || p->layer < 0 || p->layer >= p->n_layers) return CKV_EINVAL;
+  if (p->dtype != CKV_F32 && p->dtype != CKV_BF16) return CKV_EINVAL;
+  if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return CKV_EINVAL;
+  if (p->pool != CKV_POOL_NONE && p->pool != CKV_POOL_AVG && p->pool != CKV_POOL_MAX) return CKV_EINVAL;
+  if (p->pool != CKV_POOL_NONE && (p->pool_kernel < 1 || p->pool_kernel > 63 || p->pool_kernel % 2 == 0))
+    return CKV_EINVAL;
+  if (p->budget_per_kv_head < p->window) return CKV_EINVAL;
+  if (p->flags & ~(uint32_t)CKV_FLAG_VALUE_NORM) return CKV_EINVAL;
+  if (p->head_dim < 1) return CKV_EINVAL;
+  const int64_t b_tot = (int64_t)p->budget_per_kv_head * p->n_kv_heads;
+  int64_t need = b_tot - (int64_t)(p->n_kv_heads - 1) * p->window;
+  if (need > p->seq_len) need = p->seq_len;
+  if (p->cap < need) return CKV_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (p->q_stride[i] < 0 || p->k_stride[i] < 0 || p->v_stride[i] < 0) return CKV_EINVAL;
+  // rows must hold head_dim contiguous elements and start 16-byte aligned for the 128-bit loads
+  const int64_t per16 = p->dtype == CKV_BF16 ? 8 : 4;
+  if (p->q_stride[2] < p->head_dim || p->k_stride[2] < p->head_dim || p->v_stride[2] < p->head_dim)
+    return CKV_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (p->q_stride[i] % per16 || p->k_stride[i] % per16 || p->v_stride[i] % per16) return CKV_EINVAL;
+  if (p->head_dim != 64 && p->head_dim != 128) return CKV_EUNSUPPORTED;
+  if (p->window > kMaxQTiles * kTile) return CKV_EUNSUPPORTED;
+  if ((int64_t)p->batch * p->n_kv_heads > 65535) return CKV_EUNSUPPORTED;  // grid.y
+  if (p->seq_len > (1 << 24)) return CKV_EUNSUPPORTED;
+  return CKV_OK;
+}
+
+void derive(const ckv_params *p, Shape *s) {
+  s->Bz = p->batch;
+  s->Hq = p->n_q_heads;
+  s->Hkv = p->n_kv_heads;
+  s->G = s->Hq / s->Hkv;
+  s->d = p->head_dim;
+  s->T = p->seq_len;
+  s->W = p->window;
+  s->P = s->T - s->W;
+  s->esize = p->dtype == CKV_BF16 ? 2 : 4;
+  s->WT = (s->W + kTile - 1) / kTile;
+  s->n_tiles = s->G * s->WT;
+  const int per_wave_max = (kMaxQTiles / s->WT) * s->WT;  // whole heads only
+  s->n_groups = (s->n_tiles + per_wave_max - 1) / per_wave_max;
+  int nq = (s->n_tiles + s->n_groups - 1) / s->n_groups;
+  nq = (nq + s->WT - 1) / s->WT * s->WT;
+  s->NQ = nq;
+  s->n_groups = (s->n_tiles + nq - 1) / nq;
+  // Split the key axis so that the grid has a few thousand workgroups, each wave sweeping at least
+  // two tiles so that loading the query rows is amortised.
+  const int64_t units = (int64_t)s->Bz * s->Hkv * s->n_groups;
+  const int64_t target_wgs = 2048;
+  int64_t kpw = ((int64_t)s->T * units + kScoreWaves * target_wgs - 1) / (kScoreWaves * target_wgs);
+  kpw = (kpw + kTile - 1) / kTile * kTile;
+  if (kpw < 2 * kTile) kpw = 2 * kTile;
+  if (kpw > 4096) kpw = 4096;
+  s->keys_per_wave = (int)kpw;
+  s->n_chunks = (int)((s->T + kScoreWaves * kpw - 1) / (kScoreWaves * kpw));
+  s->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)s->d);
+}
+
+int vnorm_blocks_per_unit(const Shape &s) {
+  const int rows_per_block = 1024;
+  return (s.T + rows_per_block - 1) / rows_per_block;
+}
+
+void layout(const ckv_params *p, const Shape &s, Workspace *w) {
+  const size_t units = (size_t)s.Bz * s.Hkv;
+  size_t off = 0;
+  w->part_off = off;
+  w->part_bytes = units * (size_t)s.n_groups * s.NQ * kTile * s.n_chunks * sizeof(float2);
+  off = align256(off + w->part_bytes);
+  w->lse_off = off;
+  w->lse_bytes = (size_t)s.Bz * s.Hq * s.W * sizeof(float);
+  off = align256(off + w->lse_bytes);
+  w->vsum_off = off;
+  w->vsum_bytes = (p->flags & CKV_FLAG_VALUE_NORM) ? units * vnorm_blocks_per_unit(s) * sizeof(float) : 0;
+  off = align256(off + w->vsum_bytes);
+  w->total = off;
+}
+
+static ckv_status workspace_ok(const Workspace &w, const void *ws, size_t bytes) {
+  if (!ws || ((uintptr_t)ws & 255) || bytes < w.total) return CKV_EWORKSPACE;
+  return CKV_OK;
+}
+
+}  // namespace ckv
+
+using namespace ckv;
+
+extern "C" size_t ckv_workspace_bytes(const ckv_params *params) {
+  if (validate(params) != CKV_OK) return 0;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  return w.total;
+}
+
+extern "C" ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const void *k,
+                                        const void *v, const float *lse, float *scores,
+                                        float *vnorm_ratio, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!q_win || !k || !scores) return CKV_EINVAL;
+  const bool vn = params->flags & CKV_FLAG_VALUE_NORM;
+  if (vn && (!v || !vnorm_ratio)) return CKV_EINVAL;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  st = workspace_ok(w, workspace, workspace_bytes);
+  if (st != CKV_OK) return st;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (launch_window_scores(params, s, w, q_win, k, lse, scores, (char *)workspace, stream) != hipSuccess)
+    return CKV_EHIP;
+  if (vn && launch_value_norm(params, s, w, v, vnorm_ratio, (char *)workspace, stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_apply_tables(const ckv_params *params, const float *scores,
+                                       const float *vnorm_ratio, const float *w_head,
+                                       const float *head_share, const float *t_gate, int32_t n_ent,
+                                       int32_t n_ppl, const int32_t *risk_bins, float *utility,
+                                       int32_t *budget, float *tau, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!scores || !w_head || !utility || !budget || !tau) return CKV_EINVAL;
+  if ((params->flags & CKV_FLAG_VALUE_NORM) && !vnorm_ratio) return CKV_EINVAL;
+  if (t_gate && (n_ent < 1 || n_ppl < 1 || !risk_bins)) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_apply_tables(params, s, scores, vnorm_ratio, w_head, head_share, t_gate, n_ent, n_ppl,
+                          risk_bins, utility, budget, tau, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_select_topk(const ckv_params *params, const float *utility,
+                                      const int32_t *budget, const float *tau, int32_t *idx,
+                                      int32_t *count, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!utility || !budget || !tau || !idx || !count) return CKV_EINVAL;
+  (void)workspace;  // the selection keeps its histograms in LDS; the argument is reserved
+  (void)workspace_bytes;
+  Shape s;
+  derive(params, &s);
+  if (launch_select(params, s, utility, budget, tau, idx, count, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_compact_kv(const ckv_params *params, const void *k, const void *v,
+                                     const int32_t *idx, const int32_t *count, void *k_out,
+                                     void *v_out, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!k || !v || !idx || !count || !k_out || !v_out) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_gather(params, s, k, v, idx, count, k_out, v_out, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" const char *ckv_status_string(ckv_status status) {
+  switch (status) {
+    case CKV_OK: return "ok";
+    case CKV_EINVAL: return "invalid argument";
+    case CKV_EUNSUPPORTED: return "unsupported configuration";
+    case CKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case CKV_EHIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}

@@ -1,0 +1,66 @@
+// Private declarations shared by the HIP translation units of libckv (not part of the ABI).
+#ifndef CKV_INTERNAL_H_
+#define CKV_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ckv.h"
+
+namespace ckv {
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kTile = 32;          // MFMA 32x32 tile edge: query rows and keys per tile
+constexpr int kMaxQTiles = 4;      // query-row tiles a wave keeps in registers
+constexpr int kScoreWaves = 4;     // waves per workgroup in the scan kernels
+constexpr int kSelectThreads = 1024;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kValueNormEps = 1e-6f;
+
+// Derived quantities every entry point needs; filled by derive() after validation.
+struct Shape {
+  int Bz, Hq, Hkv, G, d, T, W, P;
+  int esize;        // bytes per element of Q/K/V
+  int WT;           // 32-row tiles per query head = ceil(W / 32)
+  int n_tiles;      // G * WT, query-row tiles per KV head
+  int NQ;           // tiles per wave (multiple of WT, <= kMaxQTiles)
+  int n_groups;     // ceil(n_tiles / NQ): how often K is swept for one KV head
+  int keys_per_wave;
+  int n_chunks;     // workgroups along the key axis per (unit, group)
+  float scale;      // softmax scale
+};
+
+ckv_status validate(const ckv_params *p);
+void derive(const ckv_params *p, Shape *s);
+
+// Workspace layout (bytes, 256-aligned sections), all sized from Shape.
+struct Workspace {
+  size_t part_off, part_bytes;   // float2 [units][n_tiles*32][n_chunks] row-stat partials
+  size_t lse_off, lse_bytes;     // float  [Bz][Hq][W]
+  size_t vsum_off, vsum_bytes;   // float  [units][vnorm blocks] partial sums of value norms
+  size_t total;
+};
+void layout(const ckv_params *p, const Shape &s, Workspace *w);
+int vnorm_blocks_per_unit(const Shape &s);
+
+// Kernel launchers (each returns hipGetLastError() after its launches).
+hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Workspace &w, const void *q,
+                                const void *k, const float *lse_in, float *scores, char *ws,
+                                hipStream_t stream);
+hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspace &w, const void *v,
+                             float *ratio, char *ws, hipStream_t stream);
+hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,
+                               const float *vnorm_ratio, const float *w_head, const float *head_share,
+                               const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
+                               float *utility, int32_t *budget, float *tau, hipStream_t stream);
+hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utility,
+                         const int32_t *budget, const float *tau, int32_t *idx, int32_t *count,
+                         hipStream_t stream);
+hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, const void *v,
+                         const int32_t *idx, const int32_t *count, void *k_out, void *v_out,
+                         hipStream_t stream);
+
+}  // namespace ckv
+#endif

@@ -1,0 +1,428 @@
+// Observation-window scan (paper Sec. 3 attention definition, Eq. 3, Eq. 4's alpha per query head):
+//   pass 1  rowstats_kernel : stream K, QK^T on the matrix cores, online (max, sum) per window row
+//           lse_kernel      : merge the per-chunk partials into LSE_j
+//   pass 2  colsum_kernel   : stream K again, recompute QK^T, exp(z - LSE_j), sum over window rows
+// plus the value-norm ratio rho of Eq. 4 (two small kernels).
+//
+// Work decomposition. A "unit" is one (batch, KV head): its G*W window query rows all contract with
+// the same K. Rows are cut into 32-row tiles (one MFMA 32x32 edge), whole heads only; a wave keeps up
+// to four tiles of Q in registers for its lifetime and streams 32-key tiles of K straight from
+// global memory into MFMA operand layout: lane (m, hh) = (lane % 32, lane / 32) owns row m of a tile
+// and the 16-byte chunks 2c+hh of that row. The contraction index may be permuted freely as long as
+// both operands use the same permutation, so whole 16-byte chunks become MFMA k-groups and no LDS
+// transpose is needed. The four waves of a workgroup sweep four adjacent key ranges.
+//
+// The two passes use opposite operand orders on purpose:
+//   pass 1: D = K Q^T, lane <-> query row: the running (max, sum) of a row never leaves its lane;
+//   pass 2: D = Q K^T, lane <-> key: the sum over window rows is 16 in-lane adds and one swap.
+#include "ckv_internal.h"
+
+namespace ckv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t chunk_t;  // 16 bytes of one Q or K row
+
+struct ScoreArgs {
+  const char *q, *k;
+  int64_t qs_b, qs_h, qs_w;  // byte strides
+  int64_t ks_b, ks_h, ks_t;
+  int Hq, Hkv, G, T, W, P;
+  int WT, n_tiles, n_groups, keys_per_wave, n_chunks;
+  float c2;     // softmax scale * log2(e): logits are kept in the log2 domain
+  float norm;   // T / W
+  float2 *part;      // [unit][group][NQ*32][n_chunks] (max, sum) in the log2 domain
+  const float *lse;  // [Bz][Hq][W] natural log
+  float *lse_out;
+  float *scores;     // [Bz][Hq][T]
+};
+
+template <int DT> struct Mma;
+template <> struct Mma<CKV_BF16> {
+  static __device__ __forceinline__ void step(f32x16 &acc, const chunk_t &a, const chunk_t &b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                  __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  }
+};
+template <> struct Mma<CKV_F32> {
+  static __device__ __forceinline__ void step(f32x16 &acc, const chunk_t &a, const chunk_t &b) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      // copy the lanes out first: a bit_cast applied directly to a vector element reads element 0
+      const uint32_t ua = a[e], ub = b[e];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ua), __uint_as_float(ub), acc, 0, 0, 0);
+    }
+  }
+};
+
+// Row of the 32x32 accumulator that element r of lane (m, hh) holds; its column is m.
+__device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
+
+__device__ __forceinline__ void merge_stats(float &m, float &l, float om, float ol) {
+  const float mn = fmaxf(m, om);
+  l = l * __builtin_amdgcn_exp2f(m - mn) + ol * __builtin_amdgcn_exp2f(om - mn);
+  m = mn;
+}
+
+template <int NCH>
+__device__ __forceinline__ void load_row(chunk_t (&f)[NCH], const char *row, int hh) {
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) f[c] = *reinterpret_cast<const chunk_t *>(row + (2 * c + hh) * 16);
+}
+
+struct BlockCoord {
+  int chunk, grp, unit, b, g;
+};
+__device__ __forceinline__ BlockCoord decode_block(const ScoreArgs &a) {
+  BlockCoord c;
+  int bid = blockIdx.x;
+  c.chunk = bid % a.n_chunks;
+  bid /= a.n_chunks;
+  c.grp = bid % a.n_groups;
+  c.unit = bid / a.n_groups;
+  c.b = c.unit / a.Hkv;
+  c.g = c.unit % a.Hkv;
+  return c;
+}
+
+// Loads this lane's rows of the group's NQ query tiles; jrow[i] = window row index of tile i, row m
+// (or -1 where the tile or the row is padding).
+template <int NCH, int NQ>
+__device__ __forceinline__ void load_q_tiles(const ScoreArgs &a, const BlockCoord &bc, int m, int hh,
+                                             chunk_t (&qf)[NQ][NCH], int (&jrow)[NQ]) {
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int tile = bc.grp * NQ + i;
+    const int j = (tile % a.WT) * kTile + m;
+    const bool valid = tile < a.n_tiles && j < a.W;
+    jrow[i] = valid ? j : -1;
+    if (valid) {
+      const int h = bc.g * a.G + tile / a.WT;
+      load_row<NCH>(qf[i], a.q + bc.b * a.qs_b + h * a.qs_h + j * a.qs_w, hh);
+    } else {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) qf[i][c] = chunk_t{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
+template <int DT, int DH, int NQ>
+__global__ void __launch_bounds__(kScoreWaves *kWave) rowstats_kernel(ScoreArgs a) {
+  constexpr int NCH = DH * (DT == CKV_BF16 ? 2 : 4) / 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, hh = lane >> 5;
+  const BlockCoord bc = decode_block(a);
+
+  chunk_t qf[NQ][NCH];
+  int jrow[NQ], limit[NQ];
+  load_q_tiles<NCH, NQ>(a, bc, m, hh, qf, jrow);
+  float rm[NQ], rl[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    limit[i] = jrow[i] < 0 ? -1 : a.P + jrow[i];  // last key this row may see (causal)
+    rm[i] = -1e30f;
+    rl[i] = 0.0f;
+  }
+
+  const char *kbase = a.k + bc.b * a.ks_b + bc.g * a.ks_h;
+  const int t_begin = (bc.chunk * kScoreWaves + wave) * a.keys_per_wave;
+  const int t_end = min(t_begin + a.keys_per_wave, a.T);
+  chunk_t kf[NCH];
+  if (t_begin < t_end) load_row<NCH>(kf, kbase + (int64_t)min(t_begin + m, a.T - 1) * a.ks_t, hh);
+  for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
+    chunk_t kn[NCH];
+    const int tn = t0 + kTile < t_end ? t0 + kTile : t0;
+    load_row<NCH>(kn, kbase + (int64_t)min(tn + m, a.T - 1) * a.ks_t, hh);
+    const bool edge = t0 + kTile > a.P;  // the tile touches the window (causal mask) or the end
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) Mma<DT>::step(acc, kf[c], qf[i][c]);  // rows: keys, cols: q rows
+      float x[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x[r] = acc[r] * a.c2;
+      if (edge) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (t0 + acc_row(r, hh) > limit[i]) x[r] = -INFINITY;
+      }
+      float tmax = x[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, x[r]);
+      const float mn = fmaxf(rm[i], tmax);
+      float sum = 0.0f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(x[r] - mn);
+      rl[i] = rl[i] * __builtin_amdgcn_exp2f(rm[i] - mn) + sum;
+      rm[i] = mn;
+    }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) kf[c] = kn[c];
+  }
+
+  __shared__ float2 sm[kScoreWaves][NQ * kTile];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const float om = __shfl_xor(rm[i], 32), ol = __shfl_xor(rl[i], 32);
+    merge_stats(rm[i], rl[i], om, ol);
+    if (hh == 0) sm[wave][i * kTile + m] = make_float2(rm[i], rl[i]);
+  }
+  __syncthreads();
+  if (threadIdx.x < NQ * kTile) {
+    float2 s = sm[0][threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < kScoreWaves; ++w) merge_stats(s.x, s.y, sm[w][threadIdx.x].x, sm[w][threadIdx.x].y);
+    const size_t row = ((size_t)bc.unit * a.n_groups + bc.grp) * (NQ * kTile) + threadIdx.x;
+    a.part[row * a.n_chunks + bc.chunk] = s;
+  }
+}
+
+// One thread per (unit, group, tile row): LSE_j = ln2 * (M + log2 sum_c l_c 2^(m_c - M)).
+__global__ void lse_kernel(ScoreArgs a, int NQ, int n_rows_total) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= n_rows_total) return;
+  const int per_group = NQ * kTile;
+  const int in_group = row % per_group;
+  const int grp = (row / per_group) % a.n_groups;
+  const int unit = row / (per_group * a.n_groups);
+  const int tile = grp * NQ + in_group / kTile;
+  const int j = (tile % a.WT) * kTile + in_group % kTile;
+  if (tile >= a.n_tiles || j >= a.W) return;
+  const float2 *p = a.part + (size_t)row * a.n_chunks;
+  float M = -1e30f;
+  for (int c = 0; c < a.n_chunks; ++c) M = fmaxf(M, p[c].x);
+  float L = 0.0f;
+  for (int c = 0; c < a.n_chunks; ++c) L += p[c].y * __builtin_amdgcn_exp2f(p[c].x - M);
+  const int b = unit / a.Hkv, g = unit % a.Hkv, h = g * a.G + tile / a.WT;
+  a.lse_out[((size_t)b * a.Hq + h) * a.W + j] = (M + __log2f(L)) * kLn2;
+}
+
+template <int DT, int DH, int NQ>
+__global__ void __launch_bounds__(kScoreWaves *kWave) colsum_kernel(ScoreArgs a) {
+  constexpr int NCH = DH * (DT == CKV_BF16 ? 2 : 4) / 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, hh = lane >> 5;
+  const BlockCoord bc = decode_block(a);
+
+  chunk_t qf[NQ][NCH];
+  int jrow[NQ];
+  load_q_tiles<NCH, NQ>(a, bc, m, hh, qf, jrow);
+  // -LSE (log2 domain) of the 16 accumulator rows this lane holds in each tile; -inf on padding rows
+  float nl2[NQ][16];
+  int j0[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int tile = bc.grp * NQ + i;
+    j0[i] = (tile % a.WT) * kTile;
+    const int h = bc.g * a.G + tile / a.WT;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = j0[i] + acc_row(r, hh);
+      const bool valid = tile < a.n_tiles && j < a.W;
+      nl2[i][r] = valid ? -a.lse[((size_t)bc.b * a.Hq + h) * a.W + j] * kLog2e : -INFINITY;
+    }
+  }
+
+  const char *kbase = a.k + bc.b * a.ks_b + bc.g * a.ks_h;
+  const int t_begin = (bc.chunk * kScoreWaves + wave) * a.keys_per_wave;
+  const int t_end = min(t_begin + a.keys_per_wave, a.T);
+  chunk_t kf[NCH];
+  if (t_begin < t_end) load_row<NCH>(kf, kbase + (int64_t)min(t_begin + m, a.T - 1) * a.ks_t, hh);
+  for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
+    chunk_t kn[NCH];
+    const int tn = t0 + kTile < t_end ? t0 + kTile : t0;
+    load_row<NCH>(kn, kbase + (int64_t)min(tn + m, a.T - 1) * a.ks_t, hh);
+    const bool edge = t0 + kTile > a.P;
+    const int kt = t0 + m;  // this lane's key
+    float cs[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) Mma<DT>::step(acc, qf[i][c], kf[c]);  // rows: q rows, cols: keys
+      float s = 0.0f;
+      if (edge) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float pr = __builtin_amdgcn_exp2f(fmaf(acc[r], a.c2, nl2[i][r]));
+          s += (kt <= a.P + j0[i] + acc_row(r, hh)) ? pr : 0.0f;
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f(fmaf(acc[r], a.c2, nl2[i][r]));
+      }
+      cs[i] = s + __shfl_xor(s, 32);
+    }
+    // one output per head: add the tiles of a head (WT of them), scale by T/W, lanes 0..31 store
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      if (i % a.WT) continue;
+      float v = cs[i];
+#pragma unroll
+      for (int e = 1; e < kMaxQTiles; ++e)
+        if (e < a.WT && i + e < NQ) v += cs[(i + e) < NQ ? (i + e) : i];
+      const int tile = bc.grp * NQ + i;
+      if (tile < a.n_tiles && hh == 0 && kt < a.T) {
+        const int h = bc.g * a.G + tile / a.WT;
+        a.scores[((size_t)bc.b * a.Hq + h) * a.T + kt] = v * a.norm;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) kf[c] = kn[c];
+  }
+}
+
+template <int DT, int DH>
+static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, hipStream_t stream) {
+  const int units = s.Bz * s.Hkv;
+  const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
+#define CKV_LAUNCH_NQ(NQ)                                                                    \
+  case NQ:                                                                                   \
+    if (need_lse) {                                                                          \
+      hipLaunchKernelGGL((rowstats_kernel<DT, DH, NQ>), grid, block, 0, stream, a);          \
+      const int rows = units * s.n_groups * NQ * kTile;                                      \
+      hipLaunchKernelGGL(lse_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, a, NQ, rows); \
+    }                                                                                        \
+    hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);              \
+    break;
+  switch (s.NQ) {
+    CKV_LAUNCH_NQ(1)
+    CKV_LAUNCH_NQ(2)
+    CKV_LAUNCH_NQ(3)
+    CKV_LAUNCH_NQ(4)
+    default: return hipErrorInvalidValue;
+  }
+#undef CKV_LAUNCH_NQ
+  return hipGetLastError();
+}
+
+hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Workspace &w, const void *q,
+                                const void *k, const float *lse_in, float *scores, char *ws,
+                                hipStream_t stream) {
+  ScoreArgs a;
+  a.q = (const char *)q;
+  a.k = (const char *)k;
+  a.qs_b = p->q_stride[0] * s.esize;
+  a.qs_h = p->q_stride[1] * s.esize;
+  a.qs_w = p->q_stride[2] * s.esize;
+  a.ks_b = p->k_stride[0] * s.esize;
+  a.ks_h = p->k_stride[1] * s.esize;
+  a.ks_t = p->k_stride[2] * s.esize;
+  a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = s.G; a.T = s.T; a.W = s.W; a.P = s.P;
+  a.WT = s.WT; a.n_tiles = s.n_tiles; a.n_groups = s.n_groups;
+  a.keys_per_wave = s.keys_per_wave; a.n_chunks = s.n_chunks;
+  a.c2 = s.scale * kLog2e;
+  a.norm = (float)s.T / (float)s.W;
+  a.part = (float2 *)(ws + w.part_off);
+  a.lse_out = (float *)(ws + w.lse_off);
+  a.lse = lse_in ? lse_in : a.lse_out;
+  a.scores = scores;
+  const bool need_lse = lse_in == nullptr;
+  if (p->dtype == CKV_BF16) {
+    if (s.d == 128) return launch_scores_t<CKV_BF16, 128>(s, a, need_lse, stream);
+    return launch_scores_t<CKV_BF16, 64>(s, a, need_lse, stream);
+  }
+  if (s.d == 128) return launch_scores_t<CKV_F32, 128>(s, a, need_lse, stream);
+  return launch_scores_t<CKV_F32, 64>(s, a, need_lse, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Value-norm ratio (paper Eq. 4, Alg. 1 Stage 1): r_t = ||v_t||_2, rho_t = r_t / (mean_t r_t + eps).
+// Kernel 1 writes r_t and one partial sum per 1024-row block; kernel 2 adds the partials in a fixed
+// order (no float atomics: results are bit-stable from run to run) and divides.
+// ---------------------------------------------------------------------------------------------
+struct VnormArgs {
+  const char *v;
+  int64_t vs_b, vs_h, vs_t;  // bytes
+  int Hkv, T, n_blocks;
+  float *ratio;  // [units][T]
+  float *vsum;   // [units][n_blocks]
+};
+constexpr int kVnormRows = 1024;
+
+template <int DT, int DH>
+__global__ void __launch_bounds__(256) vnorm_rows_kernel(VnormArgs a) {
+  constexpr int LPR = DH * (DT == CKV_BF16 ? 2 : 4) / 16;  // lanes per row, 8..32
+  const int unit = blockIdx.y, blk = blockIdx.x;
+  const int b = unit / a.Hkv, g = unit % a.Hkv;
+  const char *base = a.v + b * a.vs_b + g * a.vs_h;
+  const int sub = threadIdx.x % LPR, rloc = threadIdx.x / LPR;
+  float local = 0.0f;
+  for (int r = rloc; r < kVnormRows; r += 256 / LPR) {
+    const int t = blk * kVnormRows + r;
+    float sq = 0.0f;
+    if (t < a.T) {
+      const chunk_t c = *reinterpret_cast<const chunk_t *>(base + (int64_t)t * a.vs_t + sub * 16);
+      if (DT == CKV_BF16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t pair = c[e];
+          const float lo = __uint_as_float(pair << 16);
+          const float hi = __uint_as_float(pair & 0xffff0000u);
+          sq = fmaf(lo, lo, sq);
+          sq = fmaf(hi, hi, sq);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t word = c[e];
+          const float x = __uint_as_float(word);
+          sq = fmaf(x, x, sq);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+    if (sub == 0 && t < a.T) {
+      const float nrm = sqrtf(sq);
+      a.ratio[(size_t)unit * a.T + t] = nrm;
+      local += nrm;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) local += __shfl_xor(local, o);
+  __shared__ float sm[4];
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = local;
+  __syncthreads();
+  if (threadIdx.x == 0) a.vsum[(size_t)unit * a.n_blocks + blk] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
+__global__ void __launch_bounds__(256) vnorm_scale_kernel(VnormArgs a) {
+  const int unit = blockIdx.y, blk = blockIdx.x;
+  float total = 0.0f;
+  for (int i = 0; i < a.n_blocks; ++i) total += a.vsum[(size_t)unit * a.n_blocks + i];
+  const float inv = 1.0f / (total / (float)a.T + kValueNormEps);
+  for (int r = threadIdx.x; r < kVnormRows; r += 256) {
+    const int t = blk * kVnormRows + r;
+    if (t < a.T) a.ratio[(size_t)unit * a.T + t] *= inv;
+  }
+}
+
+hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspace &w, const void *v,
+                             float *ratio, char *ws, hipStream_t stream) {
+  VnormArgs a;
+  a.v = (const char *)v;
+  a.vs_b = p->v_stride[0] * s.esize;
+  a.vs_h = p->v_stride[1] * s.esize;
+  a.vs_t = p->v_stride[2] * s.esize;
+  a.Hkv = s.Hkv;
+  a.T = s.T;
+  a.n_blocks = vnorm_blocks_per_unit(s);
+  a.ratio = ratio;
+  a.vsum = (float *)(ws + w.vsum_off);
+  const dim3 grid(a.n_blocks, s.Bz * s.Hkv), block(256);
+  if (p->dtype == CKV_BF16) {
+    if (s.d == 128) hipLaunchKernelGGL((vnorm_rows_kernel<CKV_BF16, 128>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((vnorm_rows_kernel<CKV_BF16, 64>), grid, block, 0, stream, a);
+  } else {
+    if (s.d == 128) hipLaunchKernelGGL((vnorm_rows_kernel<CKV_F32, 128>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((vnorm_rows_kernel<CKV_F32, 64>), grid, block, 0, stream, a);
+  }
+  hipLaunchKernelGGL(vnorm_scale_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace ckv

@@ -1,0 +1,216 @@
+// Elastic candidate pool with budget clamp (paper Eq. 8, Alg. 1 Select) as a radix select.
+//
+// One 1024-thread workgroup per (batch, KV head). Utilities are non-negative floats, so their bit
+// patterns order like unsigned integers. The kp-th largest candidate key is found MSB-first, eight
+// bits at a time, with a 256-bin LDS histogram per pass (integer LDS atomics: the counts, and so
+// the result, do not depend on scheduling). The final pass emits the kept positions in ascending
+// order: each wave owns a contiguous range of positions, counts its keepers, and after one scan over
+// the 16 wave totals writes them out with ballot/popcount ranks. Equal keys at the threshold are taken
+// lowest position first, which is exactly "utility descending, position ascending".
+#include "ckv_internal.h"
+
+namespace ckv {
+
+struct SelectArgs {
+  const float *utility;   // [units][P]
+  const int32_t *budget;  // [units]
+  const float *tau;       // [Bz]
+  int32_t *idx;           // [units][cap]
+  int32_t *count;         // [units]
+  int Hkv, T, W, P, cap;
+};
+
+__device__ __forceinline__ uint32_t key_of(float u) {
+  const uint32_t bits = __builtin_bit_cast(uint32_t, u);
+  return (bits & 0x80000000u) ? 0u : bits;  // -0.0 orders like +0.0
+}
+
+// Executed by wave 0. Scans hist[255..0]; returns through LDS the bin where the running count first
+// reaches k (1-based) and the count strictly above that bin, plus the grand total.
+struct BinResult {
+  int bin, above, total;
+};
+__device__ __forceinline__ BinResult find_bin(const int *hist, int k, int lane) {
+  // lane i owns bins 255-4i .. 252-4i (descending)
+  int c[4], sum = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    c[e] = hist[255 - 4 * lane - e];
+    sum += c[e];
+  }
+  int incl = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  BinResult r;
+  r.total = __shfl(incl, 63);
+  const int excl = incl - sum;
+  const bool mine = excl < k && k <= incl;
+  int bin = -1, above = 0;
+  if (mine) {
+    int run = excl;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (bin < 0 && run + c[e] >= k) {
+        bin = 255 - 4 * lane - e;
+        above = run;
+      }
+      run += c[e];
+    }
+  }
+  const unsigned long long who = __ballot(mine);
+  const int src = who ? __ffsll((long long)who) - 1 : 0;
+  r.bin = __shfl(bin, src);
+  r.above = __shfl(above, src);
+  if (!who) r.bin = -1;
+  return r;
+}
+
+__global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
+  __shared__ int hist[256];
+  __shared__ int wave_gt[kSelectThreads / kWave], wave_eq[kSelectThreads / kWave];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_k, s_state;  // s_state: 0 = keep all candidates, 1 = select, 2 = keep none
+
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int P = a.P, W = a.W;
+  const float *u = a.utility + (size_t)unit * P;
+  const float tau = a.tau[unit / a.Hkv];
+  int bud = a.budget[unit];
+  bud = max(W, min(bud, min(a.cap, a.T)));
+  const int kp = bud - W;
+
+  // pass 0: histogram of the top byte over the candidates (also counts them)
+  if (tid < 256) hist[tid] = 0;
+  __syncthreads();
+  for (int t = tid; t < P; t += kSelectThreads) {
+    const float x = u[t];
+    if (x >= tau) atomicAdd(&hist[key_of(x) >> 24], 1);
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const BinResult r = find_bin(hist, max(kp, 1), lane);
+    if (lane == 0) {
+      if (r.total <= kp) s_state = 0;
+      else if (kp == 0) s_state = 2;
+      else {
+        s_state = 1;
+        s_prefix = (uint32_t)r.bin << 24;
+        s_k = kp - r.above;  // still needed from inside the chosen bin
+      }
+    }
+  }
+  __syncthreads();
+  const int state = s_state;
+
+  uint32_t thr = 0u;   // keep-all: every candidate has key > 0 or ties at 0 with unlimited quota
+  int need_eq = 0x7fffffff;
+  if (state == 2) {
+    thr = 0xffffffffu;
+    need_eq = 0;
+  } else if (state == 1) {
+    for (int shift = 16; shift >= 0; shift -= 8) {
+      const uint32_t prefix = s_prefix;
+      const int k = s_k;
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      const uint32_t hi_mask = 0xffffffffu << (shift + 8);
+      for (int t = tid; t < P; t += kSelectThreads) {
+        const float x = u[t];
+        const uint32_t key = key_of(x);
+        if (x >= tau && (key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        const BinResult r = find_bin(hist, k, lane);
+        if (lane == 0) {
+          s_prefix = prefix | ((uint32_t)r.bin << shift);
+          s_k = k - r.above;
+        }
+      }
+      __syncthreads();
+    }
+    thr = s_prefix;
+    need_eq = s_k;  // how many keys equal to thr are kept (>= 1)
+  }
+
+  // Final pass. Wave w owns positions [w*seg, (w+1)*seg); seg is a multiple of 64.
+  const int n_waves = kSelectThreads / kWave;
+  const int seg = ((P + n_waves - 1) / n_waves + kWave - 1) / kWave * kWave;
+  const int lo = wave * seg, hi = min(lo + seg, P);
+  int n_gt = 0, n_eq = 0;
+  for (int t0 = lo; t0 < hi; t0 += kWave) {
+    const int t = t0 + lane;
+    bool gt = false, eq = false;
+    if (t < hi) {
+      const float x = u[t];
+      const uint32_t key = key_of(x);
+      const bool cand = x >= tau;
+      gt = cand && key > thr;
+      eq = cand && key == thr;
+    }
+    n_gt += __popcll(__ballot(gt));
+    n_eq += __popcll(__ballot(eq));
+  }
+  if (lane == 0) {
+    wave_gt[wave] = n_gt;
+    wave_eq[wave] = n_eq;
+  }
+  __syncthreads();
+  int base_gt = 0, base_eq = 0;
+  for (int w = 0; w < wave; ++w) {
+    base_gt += wave_gt[w];
+    base_eq += wave_eq[w];
+  }
+  int32_t *out = a.idx + (size_t)unit * a.cap;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int t0 = lo; t0 < hi; t0 += kWave) {
+    const int t = t0 + lane;
+    bool gt = false, eq = false;
+    if (t < hi) {
+      const float x = u[t];
+      const uint32_t key = key_of(x);
+      const bool cand = x >= tau;
+      gt = cand && key > thr;
+      eq = cand && key == thr;
+    }
+    const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+    const int gt_before = base_gt + __popcll(bg & below);
+    const int eq_before = base_eq + __popcll(be & below);
+    if (gt || (eq && eq_before < need_eq)) {
+      const int pos = gt_before + min(eq_before, need_eq);
+      if (pos < kp) out[pos] = t;
+    }
+    base_gt += __popcll(bg);
+    base_eq += __popcll(be);
+  }
+  // kept prefix tokens, then the window
+  __syncthreads();
+  int tot_gt = 0, tot_eq = 0;
+  for (int w = 0; w < n_waves; ++w) {
+    tot_gt += wave_gt[w];
+    tot_eq += wave_eq[w];
+  }
+  const int kept = min(tot_gt + min(tot_eq, need_eq), kp);
+  for (int j = tid; j < W; j += kSelectThreads) out[kept + j] = P + j;
+  if (tid == 0) a.count[unit] = kept + W;
+}
+
+hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utility,
+                         const int32_t *budget, const float *tau, int32_t *idx, int32_t *count,
+                         hipStream_t stream) {
+  SelectArgs a;
+  a.utility = utility;
+  a.budget = budget;
+  a.tau = tau;
+  a.idx = idx;
+  a.count = count;
+  a.Hkv = s.Hkv; a.T = s.T; a.W = s.W; a.P = s.P;
+  a.cap = p->cap;
+  hipLaunchKernelGGL(select_kernel, dim3(s.Bz * s.Hkv), dim3(kSelectThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace ckv

@@ -1,0 +1,169 @@
+// Pooling + compiled-table application (paper Eq. 4 u = alpha * rho, Eq. 6 weighted max over heads,
+// Sec. 4.3 gate lookup; 1-D pooling and the per-head budget split are workload definitions).
+//
+// One workgroup owns one tile of kTablesTile prefix positions of one (batch, KV head). For each query
+// head of the group it stages the tile plus a halo of pool_kernel/2 positions in LDS, pools, multiplies
+// by rho and by the head's weight, and keeps the running maximum in registers, so the window mass
+// is read from HBM once and the utility written once.
+#include "ckv_internal.h"
+
+namespace ckv {
+
+constexpr int kTablesThreads = 256;
+constexpr int kTablesPerThread = 4;
+constexpr int kTablesTile = kTablesThreads * kTablesPerThread;  // 1024 positions
+constexpr int kMaxHalo = 31;                                    // pool_kernel <= 63
+
+struct TablesArgs {
+  const float *scores;  // [Bz][Hq][T]
+  const float *rho;     // [Bz][Hkv][T] or null
+  const float *w_row;   // w_head + layer*Hq
+  const float *share_row;  // head_share + layer*Hkv or null
+  const float *gate_layer; // t_gate + layer*n_ent*n_ppl or null
+  const int32_t *risk_bins;
+  int n_ent, n_ppl;
+  float *utility;  // [Bz][Hkv][P]
+  int32_t *budget;
+  float *tau;
+  int Bz, Hq, Hkv, G, T, W, P;
+  int pool, radius, kernel;
+  int B;  // nominal budget per KV head
+  int n_tiles;
+};
+
+// Per-head budgets of one batch element (same rule for every b; written per b for the ABI's layout).
+__device__ void write_budgets(const TablesArgs &a, int b) {
+  int32_t *out = a.budget + (size_t)b * a.Hkv;
+  if (!a.share_row) {
+    for (int g = 0; g < a.Hkv; ++g) out[g] = min(a.B, a.T);
+    return;
+  }
+  const long long b_tot = (long long)a.B * a.Hkv;
+  long long total = 0;
+  for (int g = 0; g < a.Hkv; ++g) {
+    double want = floor((double)a.share_row[g] * (double)b_tot);
+    if (!(want >= (double)a.W)) want = (double)a.W;
+    if (want > (double)a.T) want = (double)a.T;
+    out[g] = (int32_t)want;
+    total += out[g];
+  }
+  // "While the sum exceeds B_tot, the largest budget above W (lowest head on ties) loses one", done
+  // a level at a time: the n1 leaders drop together to the runner-up's value (never below W), or,
+  // when the excess runs out first, share it evenly with the remainder going to the lowest heads.
+  long long excess = total - b_tot;
+  while (excess > 0) {
+    int v1 = a.W, v2 = a.W, n1 = 0;
+    for (int g = 0; g < a.Hkv; ++g) v1 = max(v1, out[g]);
+    if (v1 <= a.W) break;
+    for (int g = 0; g < a.Hkv; ++g) {
+      if (out[g] == v1) ++n1;
+      else v2 = max(v2, out[g]);
+    }
+    const long long drop = v1 - v2;
+    if ((long long)n1 * drop <= excess) {
+      for (int g = 0; g < a.Hkv; ++g)
+        if (out[g] == v1) out[g] = v2;
+      excess -= (long long)n1 * drop;
+    } else {
+      const int each = (int)(excess / n1);
+      int extra = (int)(excess % n1);
+      for (int g = 0; g < a.Hkv; ++g)
+        if (out[g] == v1) {
+          out[g] = v1 - each - (extra > 0 ? 1 : 0);
+          if (extra > 0) --extra;
+        }
+      excess = 0;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kTablesThreads) tables_kernel(TablesArgs a) {
+  __shared__ float sm[kTablesTile + 2 * kMaxHalo];
+  const int unit = blockIdx.y, tile = blockIdx.x;
+  const int b = unit / a.Hkv, g = unit % a.Hkv;
+  const int t0 = tile * kTablesTile;
+
+  if (tile == 0 && g == 0 && threadIdx.x == 0) {
+    float tau = 0.0f;
+    if (a.gate_layer) {
+      const int be = min(max(a.risk_bins[2 * b], 0), a.n_ent - 1);
+      const int bp = min(max(a.risk_bins[2 * b + 1], 0), a.n_ppl - 1);
+      tau = a.gate_layer[be * a.n_ppl + bp];
+    }
+    a.tau[b] = tau;
+    write_budgets(a, b);
+  }
+  if (a.P == 0) return;
+
+  float best[kTablesPerThread];
+  float rho[kTablesPerThread];
+#pragma unroll
+  for (int e = 0; e < kTablesPerThread; ++e) {
+    best[e] = -INFINITY;
+    const int t = t0 + threadIdx.x + e * kTablesThreads;
+    rho[e] = (a.rho && t < a.P) ? a.rho[(size_t)unit * a.T + t] : 1.0f;
+  }
+  const int span = kTablesTile + 2 * a.radius;
+  const float pad = a.pool == CKV_POOL_MAX ? -INFINITY : 0.0f;
+  for (int hg = 0; hg < a.G; ++hg) {
+    const int h = g * a.G + hg;
+    const float *row = a.scores + ((size_t)b * a.Hq + h) * a.T;
+    __syncthreads();  // previous head's tile fully consumed
+    for (int i = threadIdx.x; i < span; i += kTablesThreads) {
+      const int t = t0 - a.radius + i;
+      sm[i] = (t >= 0 && t < a.P) ? row[t] : pad;  // pooling sees the prefix only
+    }
+    __syncthreads();
+    const float wgt = a.w_row[h];
+#pragma unroll
+    for (int e = 0; e < kTablesPerThread; ++e) {
+      const int i = threadIdx.x + e * kTablesThreads + a.radius;  // centre in sm
+      float c;
+      if (a.pool == CKV_POOL_AVG) {
+        c = 0.0f;
+        for (int dt = -a.radius; dt <= a.radius; ++dt) c += sm[i + dt];
+        c = c / (float)a.kernel;
+      } else if (a.pool == CKV_POOL_MAX) {
+        c = -INFINITY;
+        for (int dt = -a.radius; dt <= a.radius; ++dt) c = fmaxf(c, sm[i + dt]);
+      } else {
+        c = sm[i];
+      }
+      best[e] = fmaxf(best[e], wgt * (c * rho[e]));
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < kTablesPerThread; ++e) {
+    const int t = t0 + threadIdx.x + e * kTablesThreads;
+    if (t < a.P) a.utility[(size_t)unit * a.P + t] = best[e];
+  }
+}
+
+hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,
+                               const float *vnorm_ratio, const float *w_head, const float *head_share,
+                               const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
+                               float *utility, int32_t *budget, float *tau, hipStream_t stream) {
+  TablesArgs a;
+  a.scores = scores;
+  a.rho = (p->flags & CKV_FLAG_VALUE_NORM) ? vnorm_ratio : nullptr;
+  a.w_row = w_head + (size_t)p->layer * s.Hq;
+  a.share_row = head_share ? head_share + (size_t)p->layer * s.Hkv : nullptr;
+  a.gate_layer = t_gate ? t_gate + (size_t)p->layer * n_ent * n_ppl : nullptr;
+  a.risk_bins = risk_bins;
+  a.n_ent = n_ent;
+  a.n_ppl = n_ppl;
+  a.utility = utility;
+  a.budget = budget;
+  a.tau = tau;
+  a.Bz = s.Bz; a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = s.G; a.T = s.T; a.W = s.W; a.P = s.P;
+  a.pool = p->pool;
+  a.kernel = p->pool == CKV_POOL_NONE ? 1 : p->pool_kernel;
+  a.radius = a.kernel / 2;
+  a.B = p->budget_per_kv_head;
+  a.n_tiles = s.P > 0 ? (s.P + kTablesTile - 1) / kTablesTile : 1;
+  const dim3 grid(a.n_tiles, s.Bz * s.Hkv), block(kTablesThreads);
+  hipLaunchKernelGGL(tables_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace ckv

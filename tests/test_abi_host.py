@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the header
+declares, sizes its workspace, and rejects bad arguments before anything would be launched."""
+import ctypes
+import pathlib
+import re
+
+import pytest
+import torch
+
+from paper_2602_08686_amd import binding as B
+
+HEADER = pathlib.Path(__file__).resolve().parents[1] / "include" / "ckv.h"
+
+
+def _good(**kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=4096, window=32,
+                dtype=torch.bfloat16, pool=B.POOL_AVG, pool_kernel=7, budget=256, cap=512)
+    base.update(kw)
+    return B.make_params(**base)
+
+
+def test_exports_match_header():
+    lib = B.load()
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    declared = set(re.findall(r"\b(ckv_[a-z_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    # field order and count of ckv_params in the header vs. the ctypes mirror
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    body = re.search(r"typedef struct \{(.*?)\} ckv_params;", text, flags=re.S).group(1)
+    names = re.findall(r"\b([a-z_]+)(?:\[3\])?;", body)
+    assert names == [f[0] for f in B.CkvParams._fields_]
+    assert ctypes.sizeof(B.CkvParams) == 40 + 72 + 20 + 4  # 10 x 4, 9 x 8, 5 x 4, tail padding
+
+
+def test_status_strings():
+    assert B.status_string(B.CKV_OK) == "ok"
+    for s in range(1, 5):
+        assert B.status_string(s)
+    assert "unknown" in B.status_string(99)
+
+
+def test_workspace_bytes_is_aligned_and_scales():
+    a = B.ckv_workspace_bytes(_good())
+    b = B.ckv_workspace_bytes(_good(batch=8))
+    assert a > 0 and a % 256 == 0 and b > a
+    assert B.ckv_workspace_bytes(_good(flags=B.FLAG_VALUE_NORM)) > a
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n_q_heads=7),                 # Hq % Hkv
+    dict(window=0), dict(window=5000),  # W outside [1, T]
+    dict(pool_kernel=6),               # even kernel
+    dict(pool=5),
+    dict(budget=16),                   # B < W
+    dict(cap=100),                     # cap below the largest possible per-head budget
+    dict(layer=1, n_layers=1),
+    dict(flags=8),
+    dict(softmax_scale=-1.0),
+    dict(k_stride=(4096 * 128 * 2, 4096 * 128, 127)),   # row stride < head_dim / misaligned
+    dict(q_stride=(8 * 32 * 128, 32 * 128 + 4, 128)),   # not 16-byte aligned
+])
+def test_invalid_params_are_rejected_on_the_host(bad):
+    p = _good(**bad)
+    assert B.ckv_workspace_bytes(p) == 0
+    lib = B.load()
+    dummy = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    st = lib.ckv_window_scores(ctypes.byref(p), dummy, dummy, None, None, dummy, None, dummy, 1 << 30, None)
+    assert st == B.CKV_EINVAL
+    st = lib.ckv_compact_kv(ctypes.byref(p), dummy, dummy, dummy, dummy, dummy, dummy, None)
+    assert st == B.CKV_EINVAL
+
+
+def test_unsupported_shapes():
+    lib = B.load()
+    dummy = ctypes.c_void_p(256)
+    for kw in (dict(head_dim=96), dict(window=160, budget=256)):
+        p = _good(**kw)
+        st = lib.ckv_select_topk(ctypes.byref(p), dummy, dummy, dummy, dummy, dummy, None, 0, None)
+        assert st == B.CKV_EUNSUPPORTED
+
+
+def test_null_pointers_and_workspace_errors():
+    lib = B.load()
+    p = _good()
+    dummy = ctypes.c_void_p(256)
+    need = B.ckv_workspace_bytes(p)
+    assert lib.ckv_window_scores(ctypes.byref(p), None, dummy, None, None, dummy, None, dummy, need, None) == B.CKV_EINVAL
+    assert lib.ckv_window_scores(ctypes.byref(p), dummy, dummy, None, None, dummy, None, None, need, None) == B.CKV_EWORKSPACE
+    assert lib.ckv_window_scores(ctypes.byref(p), dummy, dummy, None, None, dummy, None, dummy, need - 1, None) == B.CKV_EWORKSPACE
+    assert lib.ckv_window_scores(ctypes.byref(p), dummy, dummy, None, None, dummy, None, ctypes.c_void_p(264), need, None) == B.CKV_EWORKSPACE
+    pv = _good(flags=B.FLAG_VALUE_NORM)
+    assert lib.ckv_window_scores(ctypes.byref(pv), dummy, dummy, None, None, dummy, None, dummy, 1 << 30, None) == B.CKV_EINVAL
+    assert lib.ckv_apply_tables(ctypes.byref(p), dummy, None, None, None, None, 0, 0, None, dummy, dummy, dummy, None) == B.CKV_EINVAL
+    assert lib.ckv_apply_tables(ctypes.byref(p), dummy, None, dummy, None, dummy, 20, 4, None, dummy, dummy, dummy, None) == B.CKV_EINVAL
+    assert lib.ckv_select_topk(ctypes.byref(p), dummy, dummy, dummy, None, dummy, None, 0, None) == B.CKV_EINVAL
+    assert lib.ckv_compact_kv(ctypes.byref(p), dummy, dummy, dummy, dummy, dummy, None, None) == B.CKV_EINVAL
+    assert lib.ckv_window_scores(None, dummy, dummy, None, None, dummy, None, dummy, need, None) == B.CKV_EINVAL
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        B.load(tmp_path / "libckv.so")
