@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefill-end retention step (window scan + tables + select + gather) on one MI355X.
+
+A step is one pass of the whole hot path over every layer of one synthetic prompt batch: for each
+layer the four C-ABI calls are queued back-to-back on one stream, every layer with its own K/V
+buffers already resident in HBM. The headline value is algorithmic bytes moved per second
+(what the method must read and write at least once, see `algorithmic_bytes`), to be read against
+the 8 TB/s HBM peak; ms per layer is reported beside it.
+
+Prints one JSON line. `--gpus N` with N > 1 is refused: this build is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def algorithmic_bytes(w, kept_rows: int, value_norm: bool) -> int:
+    """Bytes one layer must move at least once: K once, the Q window, V once only for the value-norm
+    ratio, the gathered K and V rows read and written, the index lists and counts, the tables."""
+    e = 2 if w.dtype == "bf16" else 4
+    units = w.batch * w.n_kv_heads
+    k_bytes = units * w.seq_len * w.head_dim * e
+    q_bytes = w.batch * w.n_q_heads * w.window * w.head_dim * e
+    v_bytes = k_bytes if value_norm else 0
+    gather = 2 * 2 * kept_rows * w.head_dim * e
+    idx = kept_rows * 4 + units * 4 * 2
+    tables = (w.n_q_heads + w.n_kv_heads + 80) * 4
+    return k_bytes + q_bytes + v_bytes + gather + idx + tables
+
+
+def scan_bytes(w) -> int:
+    """Algorithmic bytes of one scan launch (either pass): K once plus the Q window."""
+    e = 2 if w.dtype == "bf16" else 4
+    return (w.batch * w.n_kv_heads * w.seq_len + w.batch * w.n_q_heads * w.window) * w.head_dim * e
+
+
+def scan_flops(w) -> float:
+    return 2.0 * w.batch * w.n_q_heads * w.window * w.seq_len * w.head_dim
+
+
+def cpu_baseline(w, layer_t, tables, n_batch: int, value_norm: bool) -> dict:
+    """Times the oracle (as it stands) on the first n_batch batch elements of layer 0."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    f32 = lambda t: t.detach().cpu().to(torch.float32).contiguous().numpy()
+    raw = lambda t: (t.detach().cpu().contiguous().view(torch.int16).numpy()
+                     if t.dtype == torch.bfloat16 else t.detach().cpu().contiguous().numpy())
+    q, k, v = (layer_t[n][:n_batch] for n in ("q", "k", "v"))
+    qf, kf, vf, kb, vb = f32(q), f32(k), (f32(v) if value_norm else None), raw(k), raw(v)
+    share, gate = tables["head_share"], tables["t_gate"]
+    t0 = time.perf_counter()
+    out = oracle.retention_layer(
+        qf, kf, vb, v=vf, W=w.window, mode=w.pool, kernel=w.pool_kernel, B=w.budget, cap=w.cap,
+        w_head_row=f32(tables["w_head"][0]), share_row=None if share is None else f32(share[0]),
+        gate_layer=None if gate is None else f32(gate[0]),
+        risk_bins=None if gate is None else tables["risk_bins"].cpu().tolist()[:n_batch],
+        value_norm=value_norm, k_bits=kb)
+    dt = time.perf_counter() - t0
+    sub = w.scaled(batch=n_batch)
+    nbytes = algorithmic_bytes(sub, int(out["count"].sum()), value_norm)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"layer 0, batch elements 0..{n_batch - 1} of {w.batch} (all {w.n_kv_heads} KV heads), "
+                      f"whole chain, {dt:.2f} s",
+            "ms_per_layer_scaled": dt * 1e3 * w.batch / n_batch}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer buffers (0 = the config's depth)")
+    ap.add_argument("--value-norm", action="store_true")
+    ap.add_argument("--given-lse", action="store_true", help="caller-supplied LSE: single pass over K")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batch", type=int, default=0, help="batch elements in the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
+              "(every (layer, batch, KV head) unit is independent, see DESIGN.md on sharding).", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2602_08686_amd import binding as B
+    from paper_2602_08686_amd import workloads as wl
+
+    B.load()  # fails loudly if libckv.so has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    w = {c.name[:2]: c for c in wl.CONFIGS}[args.config]
+    n_layers = args.layers or w.n_layers
+    flags = B.FLAG_VALUE_NORM if args.value_norm else 0
+
+    tables = wl.make_tables(w, dev)
+    layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
+    q0, k0, v0 = layers[0]["q"], layers[0]["k"], layers[0]["v"]
+    params = [B.params_for(q0, k0, v0, pool=w.pool, pool_kernel=w.pool_kernel, budget=w.budget, cap=w.cap,
+                           layer=l % w.n_layers, n_layers=w.n_layers, flags=flags) for l in range(n_layers)]
+    buf = B.LayerBuffers(params[0], dev)
+    lse = None
+    if args.given_lse:
+        lse = [torch.empty(w.batch, w.n_q_heads, w.window, device=dev) for _ in range(n_layers)]
+        for l in range(n_layers):
+            B.ckv_window_lse(params[l], layers[l]["q"], layers[l]["k"], lse[l], buf.workspace)
+    torch.cuda.synchronize()
+
+    def step():
+        for l in range(n_layers):
+            t = layers[l]
+            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, buf, lse=None if lse is None else lse[l])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_layer = ms_per_step / n_layers
+    kept = int(buf.count.sum().item())
+    layer_bytes = algorithmic_bytes(w, kept, args.value_norm)
+    value = layer_bytes / (ms_per_layer * 1e-3) / 1e9
+
+    # Per-kernel timing of the two scan passes with events on the launch stream (torch's current one).
+    reps = max(2, args.steps)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    lse_buf = torch.empty(w.batch, w.n_q_heads, w.window, device=dev)
+    pairs1, pairs2 = [], []
+    for _ in range(reps):
+        for l in range(n_layers):
+            t = layers[l]
+            a, b_, c = ev(), ev(), ev()
+            a.record()
+            B.ckv_window_lse(params[l], t["q"], t["k"], lse_buf, buf.workspace)
+            b_.record()
+            B.ckv_window_scores(params[l], t["q"], t["k"], None, lse_buf, buf.scores, None, buf.workspace)
+            c.record()
+            pairs1.append((a, b_))
+            pairs2.append((b_, c))
+    torch.cuda.synchronize()
+    ms_pass1 = sum(a.elapsed_time(b_) for a, b_ in pairs1) / len(pairs1)
+    ms_pass2 = sum(a.elapsed_time(b_) for a, b_ in pairs2) / len(pairs2)
+    dominant, dom_ms = (("rowstats_kernel", ms_pass1) if ms_pass1 >= ms_pass2 and not args.given_lse
+                        else ("colsum_kernel", ms_pass2))
+    achieved = scan_bytes(w) / (dom_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "ms_per_launch": round(dom_ms, 4),
+        "scan_ms": {"rowstats+lse": round(ms_pass1, 4), "colsum": round(ms_pass2, 4)},
+        "mfma_tflops": {"rowstats": round(scan_flops(w) / (ms_pass1 * 1e-3) / 1e12, 1),
+                        "colsum": round(scan_flops(w) / (ms_pass2 * 1e-3) / 1e12, 1),
+                        "peak": MFMA_BF16_PEAK_TFLOPS},
+        "whole_pass_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+    }
+
+    out = {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) of prefill-end scan+select+gather; ms/layer beside it",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_layer": round(ms_per_layer, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers_per_step": n_layers, "batch": w.batch, "q_heads": w.n_q_heads,
+                   "kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.seq_len, "window": w.window,
+                   "budget_per_kv_head": w.budget, "pool": ["none", "avg", "max"][w.pool] + str(w.pool_kernel),
+                   "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed",
+                   "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        nb = args.cpu_batch or w.batch
+        out["cpu_baseline"] = cpu_baseline(w, layers[0], tables, nb, args.value_norm)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -37,7 +37,7 @@ extern "C" {
 typedef enum {
   CKV_OK = 0,
   CKV_EINVAL = 1,       /* a null pointer, a size or a flag outside the documented domain          */
-  CKV_EUNSUPPORTED = 2, /* valid, but not built (e.g. head_dim other than 64 / 128 / 256)          */
+  CKV_EUNSUPPORTED = 2, /* valid, but not built (e.g. head_dim other than 64 / 128, W > 128)       */
   CKV_EWORKSPACE = 3,   /* workspace missing, misaligned (256 B) or smaller than ckv_workspace_bytes */
   CKV_EHIP = 4          /* the HIP runtime refused a launch; see hipGetLastError                   */
 } ckv_status;
@@ -55,7 +55,7 @@ typedef struct {
   int32_t batch;          /* Bz >= 1                                                               */
   int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                                          */
   int32_t n_kv_heads;     /* Hkv >= 1                                                              */
-  int32_t head_dim;       /* d: 64, 128 or 256                                                     */
+  int32_t head_dim;       /* d: 64 or 128                                                          */
   int32_t seq_len;        /* T, window included; 1 <= W <= T                                       */
   int32_t window;         /* W                                                                     */
   int32_t layer;          /* row of the compiled tables used by this call, 0 <= layer < n_layers   */
@@ -106,6 +106,18 @@ ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const 
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * First half of the scan on its own: LSE_j of every window row, as defined above (the softmax
+ * normaliser of the paper's attention definition, Sec. 3), for callers that want to keep it or to
+ * overlap the two passes themselves. ckv_window_scores(lse = NULL) runs exactly this internally.
+ *
+ *   q_win, k   in   as for ckv_window_scores
+ *   lse        out  [Bz,Hq,W] fp32, natural log
+ *   workspace       ckv_workspace_bytes(params) bytes
+ */
+ckv_status ckv_window_lse(const ckv_params *params, const void *q_win, const void *k, float *lse,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Pooling, compiled-table lookups and budgets (paper Eq. 6 weighted max over heads, Sec. 4.3 gate
  * lookup, Alg. 1 Stages 2-3 up to the threshold; the 1-D pooling and the per-head budget split are
  * the build's workload definition, not the paper's).
@@ -117,7 +129,7 @@ ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const 
  *     utility[b,g,t] = max_{h in group g} fp32(w_head[layer,h] * u[h,t])
  * and
  *     tau[b]  = t_gate[layer, risk_bins[b,0], risk_bins[b,1]]       (0 if t_gate is NULL: gate off)
- *     budget[b,g]: NULL head_share => B. Else b_g = floor(head_share[layer,g] * B_tot) evaluated in
+ *     budget[b,g]: NULL head_share => min(B, T). Else b_g = floor(head_share[layer,g] * B_tot) evaluated in
  *               fp64, clamped to [W, T]; while sum_g b_g > B_tot the largest b_g that is > W (lowest
  *               g on ties) is decremented by one.
  *

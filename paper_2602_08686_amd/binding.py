@@ -19,7 +19,7 @@ CKV_F32, CKV_BF16 = 0, 1
 POOL_NONE, POOL_AVG, POOL_MAX = 0, 1, 2
 FLAG_VALUE_NORM = 1
 
-EXPORTS = ("ckv_workspace_bytes", "ckv_window_scores", "ckv_apply_tables", "ckv_select_topk",
+EXPORTS = ("ckv_workspace_bytes", "ckv_window_lse", "ckv_window_scores", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_status_string")
 
 
@@ -57,6 +57,8 @@ def load(path: Optional[Path] = None):
     lib.ckv_workspace_bytes.restype = ctypes.c_size_t
     lib.ckv_window_scores.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ckv_window_scores.restype = ctypes.c_int
+    lib.ckv_window_lse.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.ckv_window_lse.restype = ctypes.c_int
     lib.ckv_apply_tables.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.ckv_apply_tables.restype = ctypes.c_int
     lib.ckv_select_topk.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -132,6 +134,12 @@ def ckv_window_scores(params, q_win, k, v, lse, scores, vnorm_ratio, workspace, 
     _check(load().ckv_window_scores(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(v), _ptr(lse),
                                     _ptr(scores), _ptr(vnorm_ratio), _ptr(workspace), nbytes,
                                     _stream(stream)), "ckv_window_scores")
+
+
+def ckv_window_lse(params, q_win, k, lse, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().ckv_window_lse(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(lse), _ptr(workspace),
+                                 nbytes, _stream(stream)), "ckv_window_lse")
 
 
 def ckv_apply_tables(params, scores, vnorm_ratio, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,

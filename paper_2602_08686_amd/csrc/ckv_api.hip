@@ -127,9 +127,27 @@ extern "C" ckv_status ckv_window_scores(const ckv_params *params, const void *q_
   st = workspace_ok(w, workspace, workspace_bytes);
   if (st != CKV_OK) return st;
   hipStream_t stream = (hipStream_t)hip_stream;
-  if (launch_window_scores(params, s, w, q_win, k, lse, scores, (char *)workspace, stream) != hipSuccess)
+  if (launch_window_scores(params, s, w, q_win, k, lse, nullptr, scores, (char *)workspace, stream) != hipSuccess)
     return CKV_EHIP;
   if (vn && launch_value_norm(params, s, w, v, vnorm_ratio, (char *)workspace, stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_window_lse(const ckv_params *params, const void *q_win, const void *k,
+                                     float *lse, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!q_win || !k || !lse) return CKV_EINVAL;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  st = workspace_ok(w, workspace, workspace_bytes);
+  if (st != CKV_OK) return st;
+  if (launch_window_scores(params, s, w, q_win, k, nullptr, lse, nullptr, (char *)workspace,
+                           (hipStream_t)hip_stream) != hipSuccess)
     return CKV_EHIP;
   return CKV_OK;
 }

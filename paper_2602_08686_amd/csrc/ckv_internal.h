@@ -46,9 +46,10 @@ void layout(const ckv_params *p, const Shape &s, Workspace *w);
 int vnorm_blocks_per_unit(const Shape &s);
 
 // Kernel launchers (each returns hipGetLastError() after its launches).
+// lse_in == nullptr: pass 1 first, LSE into lse_out (or the workspace). scores == nullptr: pass 1 only.
 hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Workspace &w, const void *q,
-                                const void *k, const float *lse_in, float *scores, char *ws,
-                                hipStream_t stream);
+                                const void *k, const float *lse_in, float *lse_out, float *scores,
+                                char *ws, hipStream_t stream);
 hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspace &w, const void *v,
                              float *ratio, char *ws, hipStream_t stream);
 hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,

@@ -276,7 +276,8 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_kernel(ScoreArgs a)
 }
 
 template <int DT, int DH>
-static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, hipStream_t stream) {
+static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
+                                  hipStream_t stream) {
   const int units = s.Bz * s.Hkv;
   const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
 #define CKV_LAUNCH_NQ(NQ)                                                                    \
@@ -286,7 +287,7 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, h
       const int rows = units * s.n_groups * NQ * kTile;                                      \
       hipLaunchKernelGGL(lse_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, a, NQ, rows); \
     }                                                                                        \
-    hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);              \
+    if (need_scores) hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a); \
     break;
   switch (s.NQ) {
     CKV_LAUNCH_NQ(1)
@@ -300,8 +301,8 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, h
 }
 
 hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Workspace &w, const void *q,
-                                const void *k, const float *lse_in, float *scores, char *ws,
-                                hipStream_t stream) {
+                                const void *k, const float *lse_in, float *lse_out, float *scores,
+                                char *ws, hipStream_t stream) {
   ScoreArgs a;
   a.q = (const char *)q;
   a.k = (const char *)k;
@@ -317,16 +318,16 @@ hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Works
   a.c2 = s.scale * kLog2e;
   a.norm = (float)s.T / (float)s.W;
   a.part = (float2 *)(ws + w.part_off);
-  a.lse_out = (float *)(ws + w.lse_off);
+  a.lse_out = lse_out ? lse_out : (float *)(ws + w.lse_off);
   a.lse = lse_in ? lse_in : a.lse_out;
   a.scores = scores;
-  const bool need_lse = lse_in == nullptr;
+  const bool need_lse = lse_in == nullptr, need_scores = scores != nullptr;
   if (p->dtype == CKV_BF16) {
-    if (s.d == 128) return launch_scores_t<CKV_BF16, 128>(s, a, need_lse, stream);
-    return launch_scores_t<CKV_BF16, 64>(s, a, need_lse, stream);
+    if (s.d == 128) return launch_scores_t<CKV_BF16, 128>(s, a, need_lse, need_scores, stream);
+    return launch_scores_t<CKV_BF16, 64>(s, a, need_lse, need_scores, stream);
   }
-  if (s.d == 128) return launch_scores_t<CKV_F32, 128>(s, a, need_lse, stream);
-  return launch_scores_t<CKV_F32, 64>(s, a, need_lse, stream);
+  if (s.d == 128) return launch_scores_t<CKV_F32, 128>(s, a, need_lse, need_scores, stream);
+  return launch_scores_t<CKV_F32, 64>(s, a, need_lse, need_scores, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
