@@ -1,0 +1,84 @@
+"""GPU parity at the full sizes of the baseline configurations, in the launch configuration the
+benchmark times. The oracle is too slow for a whole layer of the large shapes, so a few seeded
+(batch, KV head) units are compared element by element and every unit is checked through
+size-independent properties plus the exact selection / gather stages."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_08686_amd import binding as B
+from paper_2602_08686_amd import workloads as wl
+from parity_util import assert_index_sets_match, assert_scores_close, bits, f32, run_gpu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+# (workload, layer, units compared element by element)
+CASES = [(wl.C2, 0, 6), (wl.C3, 0, 3), (wl.C3, 17, 2), (wl.C4, 0, 2), (wl.C4, 9, 1), (wl.C5, 0, 2), (wl.C5, 27, 1)]
+
+
+@pytest.mark.parametrize("w,layer,n_units", CASES, ids=lambda x: x.name if isinstance(x, wl.Workload) else str(x))
+def test_full_size_layer(w, layer, n_units):
+    print(f"case {w.name} layer {layer}", flush=True)
+    t = wl.make_layer(w, layer, DEV)
+    tabs = wl.make_tables(w, DEV)
+    p, buf = run_gpu(w, t, tabs, layer=layer)
+    Bz, Hq, Hkv, G, T, W, P = w.batch, w.n_q_heads, w.n_kv_heads, w.group, w.seq_len, w.window, w.prefix
+
+    # ---- properties that hold at any size, over every unit -------------------------------------
+    s = buf.scores
+    assert torch.isfinite(s).all() and (s >= 0).all()
+    np.testing.assert_allclose(s.double().sum(-1).cpu().numpy(), T, rtol=2e-4)          # Eq. 4 remark
+    budget, count, tau = buf.budget.cpu().numpy(), buf.count.cpu().numpy(), buf.tau.cpu().numpy()
+    assert (budget >= W).all() and (budget <= min(T, w.cap)).all()
+    assert (budget.sum(1) <= w.budget * Hkv).all()
+    share = tabs["head_share"]
+    ref_b = oracle.budgets(Hkv, T, W, w.budget, None if share is None else f32(share[layer]))
+    np.testing.assert_array_equal(budget, np.tile(ref_b, (Bz, 1)))
+    if tabs["t_gate"] is not None:
+        bins = tabs["risk_bins"].cpu().numpy()
+        ref_tau = [oracle.tau(f32(tabs["t_gate"][layer]), bins[b, 0], bins[b, 1]) for b in range(Bz)]
+        np.testing.assert_array_equal(tau, np.array(ref_tau, np.float32))
+    else:
+        assert (tau == 0).all()
+    ncand = (buf.utility >= buf.tau[:, None, None]).sum(-1).cpu().numpy()
+    np.testing.assert_array_equal(count, np.minimum(budget, W + ncand))                 # clamped budget
+    if w.budget == 512 and T == 32768:
+        np.testing.assert_allclose(count.sum(1) / (Hkv * T), 0.015625, atol=1e-4)        # Table A6: 1.56 %
+
+    # ---- selection and gather: exact, every unit, from the GPU's own utilities ------------------
+    util = buf.utility.cpu().numpy()
+    gi, gc = buf.idx.cpu().numpy(), count
+    oi, oc = oracle.select(util, tau, budget, W, w.cap)
+    np.testing.assert_array_equal(gc, oc)
+    np.testing.assert_array_equal(gi, oi)
+    for b in range(Bz):
+        for g in range(Hkv):
+            c = gc[b, g]
+            assert gi[b, g, c - W:c].tolist() == list(range(P, T))                        # window kept, last
+    kb, vb = bits(t["k"]), bits(t["v"])
+    np.testing.assert_array_equal(bits(buf.k_out), oracle.gather(kb, gi, gc))
+    np.testing.assert_array_equal(bits(buf.v_out), oracle.gather(vb, gi, gc))
+    del kb, vb
+    if t["needle_pos"] is not None:
+        for b in range(Bz):
+            for g in range(Hkv):
+                assert set(t["needle_pos"][b, g].tolist()) <= set(gi[b, g, : gc[b, g]].tolist())
+
+    # ---- sampled units against the oracle, element by element ------------------------------------
+    rng = np.random.default_rng(w.seed * 1000 + layer)
+    units = {0, Bz * Hkv - 1} | set(rng.integers(0, Bz * Hkv, n_units).tolist())
+    for u in sorted(units)[: max(n_units, 1)]:
+        b, g = divmod(u, Hkv)
+        print(f"  unit (b={b}, g={g})", flush=True)
+        q_u = f32(t["q"][b:b + 1, g * G:(g + 1) * G])
+        k_u = f32(t["k"][b:b + 1, g:g + 1])
+        ref_s = oracle.window_scores(q_u, k_u)
+        assert_scores_close(buf.scores[b, g * G:(g + 1) * G].cpu().numpy()[None], ref_s, f"scores unit {u}")
+        w_row = f32(tabs["w_head"][layer])[g * G:(g + 1) * G]
+        ref_u = oracle.utility(ref_s, W, 1, w.pool, w.pool_kernel, w_row)
+        assert_scores_close(util[b:b + 1, g:g + 1], ref_u.astype(np.float64), f"utility unit {u}")
+        ri, rc = oracle.select(ref_u, tau[b:b + 1], budget[b:b + 1, g:g + 1], W, w.cap)
+        assert_index_sets_match(gi[b:b + 1, g:g + 1], gc[b:b + 1, g:g + 1], ri, rc, ref_u, tau[b:b + 1],
+                                budget[b:b + 1, g:g + 1], W)
