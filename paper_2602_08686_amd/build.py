@@ -18,6 +18,13 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
+# The scan kernels never produce or consume NaN (masked logits are -inf, never inf - inf), so the
+# compiler may skip the NaN-quieting moves it otherwise puts in front of every max.
+# MFMA results stay in ordinary vector registers (the vector ALU consumes every one of them); the
+# register allocator then parks the MFMA-only operands (Q, K) in accumulation registers instead.
+EXTRA_FLAGS = {"ckv_scores.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def build_library(verbose: bool = False) -> Path:
     """Compile every source and link libckv.so. Always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -26,7 +33,8 @@ def build_library(verbose: bool = False) -> Path:
     procs = []
     for src in SOURCES:
         obj = objdir / (src + ".o")
-        cmd = [hipcc, *FLAGS, f"-I{INCLUDE}", f"-I{CSRC}", "-c", str(CSRC / src), "-o", str(obj)]
+        extra = EXTRA_FLAGS.get(src, [])
+        cmd = [hipcc, *FLAGS, *extra, f"-I{INCLUDE}", f"-I{CSRC}", "-c", str(CSRC / src), "-o", str(obj)]
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     objs = []
     for src, obj, pr in procs:

@@ -54,7 +54,10 @@ void derive(const ckv_params *p, Shape *s) {
   s->esize = p->dtype == CKV_BF16 ? 2 : 4;
   s->WT = (s->W + kTile - 1) / kTile;
   s->n_tiles = s->G * s->WT;
-  const int per_wave_max = (kMaxQTiles / s->WT) * s->WT;  // whole heads only
+  // Tiles a wave keeps in registers: four when a row is 256 bytes or less, whole heads only; rows
+  // of 512 bytes (f32, d = 128) leave room for one head's tiles only.
+  const int budget_tiles = s->d * s->esize <= 256 ? kMaxQTiles : 1;
+  const int per_wave_max = budget_tiles >= s->WT ? (budget_tiles / s->WT) * s->WT : s->WT;
   s->n_groups = (s->n_tiles + per_wave_max - 1) / per_wave_max;
   int nq = (s->n_tiles + s->n_groups - 1) / s->n_groups;
   nq = (nq + s->WT - 1) / s->WT * s->WT;
