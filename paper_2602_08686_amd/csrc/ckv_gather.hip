@@ -23,17 +23,19 @@ __global__ void __launch_bounds__(kGatherThreads) gather_kernel(GatherArgs a) {
   const int unit = blockIdx.y;
   const int n = min(a.count[unit], a.cap);
   const int rows_per_block = kGatherThreads / a.lpr;
-  const int r = blockIdx.x * rows_per_block + threadIdx.x / a.lpr;
-  if (r >= n) return;
-  const int t = a.idx[(size_t)unit * a.cap + r];
-  if (t < 0 || t >= a.T) return;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
   const int piece = (threadIdx.x % a.lpr) * 16;
-  const piece_t kk = *reinterpret_cast<const piece_t *>(a.k + b * a.ks_b + g * a.ks_h + (int64_t)t * a.ks_t + piece);
-  const piece_t vv = *reinterpret_cast<const piece_t *>(a.v + b * a.vs_b + g * a.vs_h + (int64_t)t * a.vs_t + piece);
-  const size_t o = ((size_t)unit * a.cap + r) * a.row_bytes + piece;
-  *reinterpret_cast<piece_t *>(a.k_out + o) = kk;
-  *reinterpret_cast<piece_t *>(a.v_out + o) = vv;
+  const char *kb = a.k + b * a.ks_b + g * a.ks_h + piece, *vb = a.v + b * a.vs_b + g * a.vs_h + piece;
+  // a few workgroups per unit stride over its kept rows (the count is far below cap in practice)
+  for (int r = blockIdx.x * rows_per_block + threadIdx.x / a.lpr; r < n; r += gridDim.x * rows_per_block) {
+    const int t = a.idx[(size_t)unit * a.cap + r];
+    if (t < 0 || t >= a.T) continue;
+    const piece_t kk = *reinterpret_cast<const piece_t *>(kb + (int64_t)t * a.ks_t);
+    const piece_t vv = *reinterpret_cast<const piece_t *>(vb + (int64_t)t * a.vs_t);
+    const size_t o = ((size_t)unit * a.cap + r) * a.row_bytes + piece;
+    *reinterpret_cast<piece_t *>(a.k_out + o) = kk;
+    *reinterpret_cast<piece_t *>(a.v_out + o) = vv;
+  }
 }
 
 hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, const void *v,
@@ -54,7 +56,11 @@ hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, con
   a.row_bytes = s.d * s.esize;
   a.lpr = a.row_bytes / 16;
   const int rows_per_block = kGatherThreads / a.lpr;
-  const dim3 grid((p->cap + rows_per_block - 1) / rows_per_block, s.Bz * s.Hkv), block(kGatherThreads);
+  // enough workgroups to fill the chip, at most what cap rows need
+  const int units = s.Bz * s.Hkv;
+  int per_unit = (4096 + units - 1) / units;
+  per_unit = max(1, min(per_unit, (p->cap + rows_per_block - 1) / rows_per_block));
+  const dim3 grid(per_unit, units), block(kGatherThreads);
   hipLaunchKernelGGL(gather_kernel, grid, block, 0, stream, a);
   return hipGetLastError();
 }

@@ -25,6 +25,25 @@ __device__ __forceinline__ uint32_t key_of(float u) {
   return (bits & 0x80000000u) ? 0u : bits;  // -0.0 orders like +0.0
 }
 
+// Adds one count per active lane to hist[digit]. Utilities cluster in a few exponent bins, so plain
+// per-lane LDS atomics would serialise on one address: the wave first elects up to three leaders
+// whose digit is shared by many lanes and adds a popcount for each; stragglers use their own atomic.
+// Every lane of the wave must call this (it uses ballots).
+__device__ __forceinline__ void hist_add(int *hist, bool active, int digit, int lane) {
+  unsigned long long rem = __ballot(active);
+#pragma unroll
+  for (int it = 0; it < 3; ++it) {
+    if (rem == 0) break;
+    const int leader = __ffsll((long long)rem) - 1;
+    const int d = __shfl(digit, leader);
+    const unsigned long long same = __ballot(active && digit == d);
+    if (lane == leader) atomicAdd(&hist[d], __popcll(same));
+    active = active && digit != d;
+    rem &= ~same;
+  }
+  if (active) atomicAdd(&hist[digit], 1);
+}
+
 // Executed by wave 0. Scans hist[255..0]; returns through LDS the bin where the running count first
 // reaches k (1-based) and the count strictly above that bin, plus the grand total.
 struct BinResult {
@@ -85,9 +104,10 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   // pass 0: histogram of the top byte over the candidates (also counts them)
   if (tid < 256) hist[tid] = 0;
   __syncthreads();
-  for (int t = tid; t < P; t += kSelectThreads) {
-    const float x = u[t];
-    if (x >= tau) atomicAdd(&hist[key_of(x) >> 24], 1);
+  for (int t0 = 0; t0 < P; t0 += kSelectThreads) {
+    const int t = t0 + tid;
+    const float x = t < P ? u[t] : -1.0f;
+    hist_add(hist, t < P && x >= tau, (int)(key_of(x) >> 24), lane);
   }
   __syncthreads();
   if (wave == 0) {
@@ -117,10 +137,11 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       const uint32_t hi_mask = 0xffffffffu << (shift + 8);
-      for (int t = tid; t < P; t += kSelectThreads) {
-        const float x = u[t];
+      for (int t0 = 0; t0 < P; t0 += kSelectThreads) {
+        const int t = t0 + tid;
+        const float x = t < P ? u[t] : -1.0f;
         const uint32_t key = key_of(x);
-        if (x >= tau && (key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        hist_add(hist, t < P && x >= tau && (key & hi_mask) == prefix, (int)((key >> shift) & 255u), lane);
       }
       __syncthreads();
       if (wave == 0) {

@@ -139,6 +139,85 @@ __global__ void __launch_bounds__(kTablesThreads) tables_kernel(TablesArgs a) {
   }
 }
 
+// Fast path for pooling kernels of at most 9 taps on 16-byte aligned rows (T % 4 == 0): a thread owns
+// four consecutive positions and reads them plus the four on either side as three 128-bit loads per
+// head (the neighbours' loads hit L1), pools from registers with the taps unrolled, and writes one
+// 128-bit store (or scalars where P is not a multiple of four). No LDS and no barriers.
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+template <int POOL, int R>
+__global__ void __launch_bounds__(kTablesThreads) tables_window_kernel(TablesArgs a) {
+  const int unit = blockIdx.y;
+  const int b = unit / a.Hkv, g = unit % a.Hkv;
+  const int t = (blockIdx.x * kTablesThreads + threadIdx.x) * 4;  // first of this thread's positions
+  if (blockIdx.x == 0 && g == 0 && threadIdx.x == 0) {
+    float tau = 0.0f;
+    if (a.gate_layer) {
+      const int be = min(max(a.risk_bins[2 * b], 0), a.n_ent - 1);
+      const int bp = min(max(a.risk_bins[2 * b + 1], 0), a.n_ppl - 1);
+      tau = a.gate_layer[be * a.n_ppl + bp];
+    }
+    a.tau[b] = tau;
+    write_budgets(a, b);
+  }
+  if (t >= a.P) return;
+  const float pad = POOL == CKV_POOL_MAX ? -INFINITY : 0.0f;
+  float rho[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+  if (a.rho) {
+    const f32x4_t r4 = *reinterpret_cast<const f32x4_t *>(a.rho + (size_t)unit * a.T + t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rho[e] = r4[e];
+  }
+  float best[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  for (int hg = 0; hg < a.G; ++hg) {
+    const int h = g * a.G + hg;
+    const float *row = a.scores + ((size_t)b * a.Hq + h) * a.T;
+    // w[0..11] = positions t-4 .. t+7; everything outside [0, P) counts as padding. Rows hold T >= P + 1
+    // floats and T % 4 == 0, so the three loads stay inside the row whenever their first index is < T.
+    float w[12];
+    const f32x4_t mid = *reinterpret_cast<const f32x4_t *>(row + t);
+    f32x4_t lo = {pad, pad, pad, pad}, hi = {pad, pad, pad, pad};
+    if (R > 0 && t >= 4) lo = *reinterpret_cast<const f32x4_t *>(row + t - 4);
+    if (R > 0 && t + 4 < a.T) hi = *reinterpret_cast<const f32x4_t *>(row + t + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      w[e] = lo[e];
+      w[4 + e] = (t + e < a.P) ? mid[e] : pad;
+      w[8 + e] = (t + 4 + e < a.P) ? hi[e] : pad;
+    }
+    const float wgt = a.w_row[h];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float c = w[4 + e - R];
+#pragma unroll
+      for (int d = 1 - R; d <= R; ++d) c = POOL == CKV_POOL_MAX ? fmaxf(c, w[4 + e + d]) : c + w[4 + e + d];
+      if (POOL == CKV_POOL_AVG) c = c / (float)(2 * R + 1);
+      best[e] = fmaxf(best[e], wgt * (c * rho[e]));
+    }
+  }
+  float *out = a.utility + (size_t)unit * a.P + t;
+  if (a.P % 4 == 0) {
+    *reinterpret_cast<f32x4_t *>(out) = f32x4_t{best[0], best[1], best[2], best[3]};
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (t + e < a.P) out[e] = best[e];
+  }
+}
+
+template <int POOL>
+static bool launch_window_pool(const TablesArgs &a, dim3 grid, hipStream_t stream) {
+  const dim3 block(kTablesThreads);
+  switch (a.radius) {
+    case 0: hipLaunchKernelGGL((tables_window_kernel<POOL, 0>), grid, block, 0, stream, a); return true;
+    case 1: hipLaunchKernelGGL((tables_window_kernel<POOL, 1>), grid, block, 0, stream, a); return true;
+    case 2: hipLaunchKernelGGL((tables_window_kernel<POOL, 2>), grid, block, 0, stream, a); return true;
+    case 3: hipLaunchKernelGGL((tables_window_kernel<POOL, 3>), grid, block, 0, stream, a); return true;
+    case 4: hipLaunchKernelGGL((tables_window_kernel<POOL, 4>), grid, block, 0, stream, a); return true;
+  }
+  return false;
+}
+
 hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,
                                const float *vnorm_ratio, const float *w_head, const float *head_share,
                                const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
@@ -162,7 +241,13 @@ hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float 
   a.B = p->budget_per_kv_head;
   a.n_tiles = s.P > 0 ? (s.P + kTablesTile - 1) / kTablesTile : 1;
   const dim3 grid(a.n_tiles, s.Bz * s.Hkv), block(kTablesThreads);
-  hipLaunchKernelGGL(tables_kernel, grid, block, 0, stream, a);
+  const bool aligned = s.T % 4 == 0 && ((uintptr_t)scores % 16 == 0) && ((uintptr_t)utility % 16 == 0) &&
+                       (!a.rho || (uintptr_t)a.rho % 16 == 0);
+  bool done = false;
+  if (aligned && s.P > 0 && a.radius <= 4)
+    done = p->pool == CKV_POOL_MAX ? launch_window_pool<CKV_POOL_MAX>(a, grid, stream)
+                                   : launch_window_pool<CKV_POOL_AVG>(a, grid, stream);
+  if (!done) hipLaunchKernelGGL(tables_kernel, grid, block, 0, stream, a);
   return hipGetLastError();
 }
 
