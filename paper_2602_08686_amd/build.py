@@ -10,7 +10,8 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB = PKG / "libckv.so"
-SOURCES = ["ckv_api.hip", "ckv_scores.hip", "ckv_tables.hip", "ckv_select.hip", "ckv_gather.hip"]
+SCAN_SOURCES = ["ckv_scan_bf16_d128.hip", "ckv_scan_bf16_d64.hip", "ckv_scan_f32_d64.hip", "ckv_scan_f32_d128.hip"]
+SOURCES = SCAN_SOURCES + ["ckv_api.hip", "ckv_scores.hip", "ckv_tables.hip", "ckv_select.hip", "ckv_gather.hip"]
 # Packed-FP32 instructions are switched off for the device pass (some forms have given wrong
 # results on the target machines); the host pass does not know the feature and says so, harmlessly.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -22,7 +23,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
 # compiler may skip the NaN-quieting moves it otherwise puts in front of every max.
 # MFMA results stay in ordinary vector registers (the vector ALU consumes every one of them); the
 # register allocator then parks the MFMA-only operands (Q, K) in accumulation registers instead.
-EXTRA_FLAGS = {"ckv_scores.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA_FLAGS = {src: ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"] for src in SCAN_SOURCES}
 
 
 def build_library(verbose: bool = False) -> Path:

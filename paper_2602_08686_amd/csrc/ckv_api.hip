@@ -39,6 +39,7 @@ ckv_status validate(const ckv_params *p) {
   if (p->window > kMaxQTiles * kTile) return CKV_EUNSUPPORTED;
   if ((int64_t)p->batch * p->n_kv_heads > 65535) return CKV_EUNSUPPORTED;  // grid.y
   if (p->seq_len > (1 << 24)) return CKV_EUNSUPPORTED;
+  if ((int64_t)p->n_q_heads * p->seq_len >= (1 << 29)) return CKV_EUNSUPPORTED;  // scores of one batch element: < 2 GiB
   return CKV_OK;
 }
 
@@ -63,12 +64,15 @@ void derive(const ckv_params *p, Shape *s) {
   nq = (nq + s->WT - 1) / s->WT * s->WT;
   s->NQ = nq;
   s->n_groups = (s->n_tiles + nq - 1) / nq;
-  // Split the key axis so that the grid has a few thousand workgroups, each wave sweeping at least
-  // two tiles so that loading the query rows is amortised.
+  // Split the key axis. The bf16 kernels keep one workgroup per CU busy for the whole launch (their
+  // set-up is not overlapped with anything, so there is one workgroup per CU and its waves sweep long
+  // ranges, a whole number of four-tile pipeline rounds); the f32 kernels run two workgroups per CU
+  // and like a few thousand of them.
   const int64_t units = (int64_t)s->Bz * s->Hkv * s->n_groups;
-  const int64_t target_wgs = 2048;
+  const int64_t target_wgs = p->dtype == CKV_BF16 ? kComputeUnits : 2048;
   int64_t kpw = ((int64_t)s->T * units + kScoreWaves * target_wgs - 1) / (kScoreWaves * target_wgs);
-  kpw = (kpw + kTile - 1) / kTile * kTile;
+  const int64_t quantum = p->dtype == CKV_BF16 && kpw > 4 * kTile ? 4 * kTile : kTile;
+  kpw = (kpw + quantum - 1) / quantum * quantum;
   if (kpw < 2 * kTile) kpw = 2 * kTile;
   if (kpw > 4096) kpw = 4096;
   s->keys_per_wave = (int)kpw;

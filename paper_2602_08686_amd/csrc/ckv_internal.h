@@ -14,6 +14,7 @@ constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kTile = 32;          // MFMA 32x32 tile edge: query rows and keys per tile
 constexpr int kMaxQTiles = 4;      // query-row tiles a wave keeps in registers
 constexpr int kScoreWaves = 4;     // waves per workgroup in the scan kernels
+constexpr int kComputeUnits = 256; // MI355X
 constexpr int kSelectThreads = 1024;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;

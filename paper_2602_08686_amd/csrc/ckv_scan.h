@@ -1,0 +1,869 @@
+// Kernel templates of the observation-window scan (paper Sec. 3 attention definition, Eq. 3, Eq. 4's alpha per query head):
+//   pass 1  rowstats kernels : stream K, QK^T on the matrix cores, online (max, sum) per window row
+//           lse_kernel       : merge the per-chunk partials into LSE_j
+//   pass 2  colsum kernels   : stream K again, recompute QK^T, exp(z - LSE_j), sum over window rows
+// plus the value-norm ratio rho of Eq. 4 (two small kernels).
+//
+// Work decomposition. A "unit" is one (batch, KV head): its G*W window query rows all contract with
+// the same K. Rows are cut into 32-row tiles (one MFMA 32x32 edge), whole heads only; a wave keeps up
+// to four tiles of Q in registers for its lifetime and streams 32-key tiles of K straight from
+// global memory into MFMA operand layout: lane (m, hh) = (lane % 32, lane / 32) owns row m of a tile
+// and the 16-byte chunks 2c+hh of that row. The contraction index may be permuted freely as long as
+// both operands use the same permutation, so whole 16-byte chunks become MFMA k-groups and no LDS
+// transpose is needed. The four waves of a workgroup sweep four adjacent key ranges.
+//
+// The two passes use opposite operand orders on purpose:
+//   pass 1: D = K Q^T, lane <-> query row: the running (max, sum) of a row never leaves its lane;
+//   pass 2: D = Q K^T, lane <-> key: the sum over window rows is 16 in-lane adds and one half swap.
+//
+// Two families of kernels: plain ones that load every operand straight from global memory (f32,
+// whose workloads are small), and LDS-staged, software-pipelined ones for bf16.
+#ifndef CKV_SCAN_H_
+#define CKV_SCAN_H_
+#include "ckv_internal.h"
+
+namespace ckv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t chunk_t;  // 16 bytes of one Q or K row
+
+struct ScoreArgs {
+  const char *q, *k;
+  int64_t qs_b, qs_h, qs_w;  // byte strides
+  int64_t ks_b, ks_h, ks_t;
+  int Hq, Hkv, G, T, W, P;
+  int WT, n_tiles, n_groups, keys_per_wave, n_chunks;
+  float c2;     // softmax scale * log2(e): logits are kept in the log2 domain
+  float norm;   // T / W
+  float2 *part;      // [unit][group][NQ*32][n_chunks] (max, sum) in the log2 domain
+  const float *lse;  // [Bz][Hq][W] natural log
+  float *lse_out;
+  float *scores;     // [Bz][Hq][T]
+};
+
+template <int DT> struct Mma;
+template <> struct Mma<CKV_BF16> {
+  static __device__ __forceinline__ void step(f32x16 &acc, const chunk_t &a, const chunk_t &b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                  __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  }
+};
+template <> struct Mma<CKV_F32> {
+  static __device__ __forceinline__ void step(f32x16 &acc, const chunk_t &a, const chunk_t &b) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      // copy the lanes out first: a bit_cast applied directly to a vector element reads element 0
+      const uint32_t ua = a[e], ub = b[e];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ua), __uint_as_float(ub), acc, 0, 0, 0);
+    }
+  }
+};
+
+// acc = sum over the row's chunks of a[c] . b[c]  (a: the 32 rows of D, b: the 32 columns of D)
+template <int DT, int NCH>
+__device__ __forceinline__ void mma_chain(f32x16 &acc, const chunk_t (&a)[NCH], const chunk_t (&b)[NCH]) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) Mma<DT>::step(acc, a[c], b[c]);
+}
+
+// Row of the 32x32 accumulator that element r of lane (m, hh) holds; its column is m.
+__device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
+
+__device__ __forceinline__ void merge_stats(float &m, float &l, float om, float ol) {
+  const float mn = fmaxf(m, om);
+  l = l * __builtin_amdgcn_exp2f(m - mn) + ol * __builtin_amdgcn_exp2f(om - mn);
+  m = mn;
+}
+
+template <int NCH>
+__device__ __forceinline__ void load_row(chunk_t (&f)[NCH], const char *row, int hh) {
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) f[c] = *reinterpret_cast<const chunk_t *>(row + (2 * c + hh) * 16);
+}
+
+struct BlockCoord {
+  int chunk, grp, unit, b, g;
+};
+__device__ __forceinline__ BlockCoord decode_block(const ScoreArgs &a) {
+  BlockCoord c;
+  int bid = blockIdx.x;
+  c.chunk = bid % a.n_chunks;
+  bid /= a.n_chunks;
+  c.grp = bid % a.n_groups;
+  c.unit = bid / a.n_groups;
+  c.b = c.unit / a.Hkv;
+  c.g = c.unit % a.Hkv;
+  return c;
+}
+
+// Loads this lane's rows of the group's NQ query tiles; jrow[i] = window row index of tile i, row m
+// (or -1 where the tile or the row is padding).
+template <int NCH, int NQ>
+__device__ __forceinline__ void load_q_tiles(const ScoreArgs &a, const BlockCoord &bc, int m, int hh,
+                                             chunk_t (&qf)[NQ][NCH], int (&jrow)[NQ]) {
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int tile = bc.grp * NQ + i;
+    const int j = (tile % a.WT) * kTile + m;
+    const bool valid = tile < a.n_tiles && j < a.W;
+    jrow[i] = valid ? j : -1;
+    if (valid) {
+      const int h = bc.g * a.G + tile / a.WT;
+      load_row<NCH>(qf[i], a.q + bc.b * a.qs_b + h * a.qs_h + j * a.qs_w, hh);
+    } else {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) qf[i][c] = chunk_t{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
+// Pass 1, vector part: online (max, sum) update of this lane's query row with the 16 logits it holds
+// of one tile. The maximum is taken on the raw dot products (the scale is positive); scale and
+// subtraction are one FMA per element.
+template <bool EDGE>
+__device__ __forceinline__ void rowstats_update(const f32x16 &acc, float c2, int t0, int hh, int limit,
+                                                float &rm, float &rl) {
+  float v[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = acc[r];
+  if (EDGE) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (t0 + acc_row(r, hh) > limit) v[r] = -INFINITY;
+  }
+  float t[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) t[e] = fmaxf(fmaxf(v[4 * e], v[4 * e + 1]), fmaxf(v[4 * e + 2], v[4 * e + 3]));
+  const float tmax = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
+  const float mn = fmaxf(rm, tmax * c2);
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[r & 3] += __builtin_amdgcn_exp2f(fmaf(v[r], c2, -mn));
+  rl = fmaf(rl, __builtin_amdgcn_exp2f(rm - mn), (s[0] + s[1]) + (s[2] + s[3]));
+  rm = mn;
+}
+
+// Merges the (max, sum) pairs of the two half-waves and of the workgroup's waves, one partial per chunk.
+template <int NQ>
+__device__ __forceinline__ void store_row_partials(const ScoreArgs &a, const BlockCoord &bc, int wave, int m,
+                                                   int hh, float (&rm)[NQ], float (&rl)[NQ]) {
+  __shared__ float2 sm[kScoreWaves][NQ * kTile];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const float om = __shfl_xor(rm[i], 32), ol = __shfl_xor(rl[i], 32);
+    merge_stats(rm[i], rl[i], om, ol);
+    if (hh == 0) sm[wave][i * kTile + m] = make_float2(rm[i], rl[i]);
+  }
+  __syncthreads();
+  if (threadIdx.x < NQ * kTile) {
+    float2 s = sm[0][threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < kScoreWaves; ++w) merge_stats(s.x, s.y, sm[w][threadIdx.x].x, sm[w][threadIdx.x].y);
+    const size_t row = ((size_t)bc.unit * a.n_groups + bc.grp) * (NQ * kTile) + threadIdx.x;
+    a.part[row * a.n_chunks + bc.chunk] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plain kernels: every dtype / tile count. Two waves per SIMD, K double-buffered in registers.
+// ---------------------------------------------------------------------------------------------
+template <int DT, int DH, int NQ>
+__global__ void __launch_bounds__(kScoreWaves *kWave, 2) rowstats_kernel(ScoreArgs a) {
+  constexpr int NCH = DH * (DT == CKV_BF16 ? 2 : 4) / 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, hh = lane >> 5;
+  const BlockCoord bc = decode_block(a);
+
+  chunk_t qf[NQ][NCH];
+  int jrow[NQ], limit[NQ];
+  load_q_tiles<NCH, NQ>(a, bc, m, hh, qf, jrow);
+  float rm[NQ], rl[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    limit[i] = jrow[i] < 0 ? -1 : a.P + jrow[i];  // last key this row may see (causal)
+    rm[i] = -1e30f;
+    rl[i] = 0.0f;
+  }
+
+  const char *kbase = a.k + bc.b * a.ks_b + bc.g * a.ks_h;
+  const int t_begin = (bc.chunk * kScoreWaves + wave) * a.keys_per_wave;
+  const int t_end = min(t_begin + a.keys_per_wave, a.T);
+  auto tile_body = [&](const chunk_t (&kf)[NCH], int t0) {
+    f32x16 acc;
+    if (t0 + kTile > a.P) {  // the tile touches the window (causal mask) or the end of the keys
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        mma_chain<DT, NCH>(acc, kf, qf[i]);  // rows: keys, cols: query rows
+        rowstats_update<true>(acc, a.c2, t0, hh, limit[i], rm[i], rl[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        mma_chain<DT, NCH>(acc, kf, qf[i]);
+        rowstats_update<false>(acc, a.c2, t0, hh, limit[i], rm[i], rl[i]);
+      }
+    }
+  };
+  // two K tiles in registers, used alternately: one is computed on while the other is in flight
+  chunk_t ka[NCH], kb[NCH];
+  if (t_begin < t_end) load_row<NCH>(ka, kbase + (int64_t)min(t_begin + m, a.T - 1) * a.ks_t, hh);
+  for (int t0 = t_begin; t0 < t_end; t0 += 2 * kTile) {
+    load_row<NCH>(kb, kbase + (int64_t)min(t0 + kTile + m, a.T - 1) * a.ks_t, hh);
+    tile_body(ka, t0);
+    if (t0 + kTile >= t_end) break;
+    load_row<NCH>(ka, kbase + (int64_t)min(t0 + 2 * kTile + m, a.T - 1) * a.ks_t, hh);
+    tile_body(kb, t0 + kTile);
+  }
+  store_row_partials<NQ>(a, bc, wave, m, hh, rm, rl);
+}
+
+// One thread per (unit, group, tile row): LSE_j = ln2 * (M + log2 sum_c l_c 2^(m_c - M)).
+template <int NQ>
+__global__ void lse_kernel(ScoreArgs a, int n_rows_total) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= n_rows_total) return;
+  const int per_group = NQ * kTile;
+  const int in_group = row % per_group;
+  const int grp = (row / per_group) % a.n_groups;
+  const int unit = row / (per_group * a.n_groups);
+  const int tile = grp * NQ + in_group / kTile;
+  const int j = (tile % a.WT) * kTile + in_group % kTile;
+  if (tile >= a.n_tiles || j >= a.W) return;
+  const float2 *p = a.part + (size_t)row * a.n_chunks;
+  float M = -1e30f;
+  for (int c = 0; c < a.n_chunks; ++c) M = fmaxf(M, p[c].x);
+  float L = 0.0f;
+  for (int c = 0; c < a.n_chunks; ++c) L += p[c].y * __builtin_amdgcn_exp2f(p[c].x - M);
+  const int b = unit / a.Hkv, g = unit % a.Hkv, h = g * a.G + tile / a.WT;
+  a.lse_out[((size_t)b * a.Hq + h) * a.W + j] = (M + __log2f(L)) * kLn2;
+}
+
+// One 32-row x 32-key tile of pass 2 for the plain kernel. The accumulator starts at -LSE_row / scale
+// (read from LDS before the MFMA chain, so the LDS latency hides behind it), the chain adds <q, k>, and
+// the weight is exp2(c2 * acc) = exp(z - LSE). Returns this lane's sum over its 16 rows.
+template <int DT, int NCH, bool EDGE>
+__device__ __forceinline__ float colsum_tile(const chunk_t (&qf)[NCH], const chunk_t (&kf)[NCH], float c2,
+                                             const float *init_tile, int hh, int first_masked_row) {
+  f32x16 acc;
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const f32x4 ini = *reinterpret_cast<const f32x4 *>(init_tile + 8 * q4 + 4 * hh);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[4 * q4 + e] = ini[e];
+  }
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) Mma<DT>::step(acc, qf[c], kf[c]);  // rows: query rows, cols: keys
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float pr = __builtin_amdgcn_exp2f(acc[r] * c2);
+    // causal: key kt is visible to window row j iff kt <= P + j, i.e. tile row >= kt - P - j0
+    if (EDGE && acc_row(r, hh) < first_masked_row) pr = 0.0f;
+    s[r & 3] += pr;
+  }
+  return (s[0] + s[1]) + (s[2] + s[3]);
+}
+
+template <int DT, int DH, int NQ>
+__global__ void __launch_bounds__(kScoreWaves *kWave, 2) colsum_kernel(ScoreArgs a) {
+  constexpr int NCH = DH * (DT == CKV_BF16 ? 2 : 4) / 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, m = lane & 31, hh = lane >> 5;
+  const BlockCoord bc = decode_block(a);
+
+  // accumulator start value -LSE / scale of every row of the group's tiles; -inf on padding rows so
+  // that their weights come out as exp2(-inf) = 0
+  __shared__ __attribute__((aligned(16))) float s_init[NQ * kTile];
+  if (threadIdx.x < NQ * kTile) {
+    const int tile = bc.grp * NQ + threadIdx.x / kTile;
+    const int j = (tile % a.WT) * kTile + threadIdx.x % kTile;
+    const int h = bc.g * a.G + tile / a.WT;
+    const bool valid = tile < a.n_tiles && j < a.W;
+    s_init[threadIdx.x] = valid ? -a.lse[((size_t)bc.b * a.Hq + h) * a.W + j] * (kLog2e / a.c2) : -INFINITY;
+  }
+  chunk_t qf[NQ][NCH];
+  int jrow[NQ];
+  load_q_tiles<NCH, NQ>(a, bc, m, hh, qf, jrow);
+  __syncthreads();
+
+  const char *kbase = a.k + bc.b * a.ks_b + bc.g * a.ks_h;
+  const int t_begin = (bc.chunk * kScoreWaves + wave) * a.keys_per_wave;
+  const int t_end = min(t_begin + a.keys_per_wave, a.T);
+
+  auto tile_body = [&](const chunk_t (&kf)[NCH], int t0) {
+    const int kt = t0 + m;  // this lane's key
+    float cs[NQ];
+    if (t0 + kTile > a.P) {
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        const int j0 = ((bc.grp * NQ + i) % a.WT) * kTile;
+        cs[i] = colsum_tile<DT, NCH, true>(qf[i], kf, a.c2, s_init + i * kTile, hh, kt - a.P - j0);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) cs[i] = colsum_tile<DT, NCH, false>(qf[i], kf, a.c2, s_init + i * kTile, hh, 0);
+    }
+    // the other half-wave holds the other 16 rows of each tile: swap and add (all swaps in flight together)
+    float other[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) other[i] = __shfl_xor(cs[i], 32);
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) cs[i] += other[i];
+    // one output per head: add the tiles of a head (WT of them), scale by T/W, lanes 0..31 store
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      if (i % a.WT) continue;
+      float v = cs[i];
+#pragma unroll
+      for (int e = 1; e < kMaxQTiles; ++e)
+        if (e < a.WT && i + e < NQ) v += cs[(i + e) < NQ ? (i + e) : i];
+      const int tile = bc.grp * NQ + i;
+      if (tile < a.n_tiles && hh == 0 && kt < a.T) {
+        const int h = bc.g * a.G + tile / a.WT;
+        a.scores[((size_t)bc.b * a.Hq + h) * a.T + kt] = v * a.norm;
+      }
+    }
+  };
+
+  chunk_t ka[NCH], kb[NCH];
+  if (t_begin < t_end) load_row<NCH>(ka, kbase + (int64_t)min(t_begin + m, a.T - 1) * a.ks_t, hh);
+  for (int t0 = t_begin; t0 < t_end; t0 += 2 * kTile) {
+    load_row<NCH>(kb, kbase + (int64_t)min(t0 + kTile + m, a.T - 1) * a.ks_t, hh);
+    tile_body(ka, t0);
+    if (t0 + kTile >= t_end) break;
+    load_row<NCH>(ka, kbase + (int64_t)min(t0 + 2 * kTile + m, a.T - 1) * a.ks_t, hh);
+    tile_body(kb, t0 + kTile);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS-staged kernels for bf16 (rows of 128 or 256 bytes).
+//
+// A load instruction in which every lane addresses a different row touches 32 cache lines and keeps
+// the texture-address unit busy several times longer than a contiguous one; with four waves per CU
+// the scan then runs at the address unit's pace. These kernels therefore move K (and once per
+// workgroup, Q) with global -> LDS loads in which the 64 lanes of one instruction read 1 KiB of whole
+// rows, and pick the MFMA operand layout up from LDS with 128-bit reads. Each wave owns a ring of
+// four tile images. The image of a 32-row tile holds chunk kappa of row r at
+// r * ROW + ((kappa ^ (r & SW)) * 16) so that the operand reads (32 lanes, same chunk, consecutive
+// rows) spread over all banks; the load writes lane l's 16 bytes at image offset 16 * (64 * i + l),
+// so the swizzle is applied to the source address instead.
+//
+// One wave per SIMD runs a two-stage software pipeline over (key tile, query tile) pairs: the MFMA
+// chain of the next pair is issued in between the vector instructions that consume the current
+// pair's logits (two accumulator sets). A lone wave issues one instruction at a time, so everything
+// that is not vector arithmetic is kept out of the loop: the loop is unrolled over the ring (image
+// addresses become immediates), key tiles are addressed by a running scalar pointer, and the loads
+// use the scalar-base form with one M0 write per four instructions (their immediate offset moves the
+// global and the LDS address alike, which the per-lane offsets compensate). In pass 2 the -LSE of the
+// accumulator rows is folded into the contraction as one more MFMA step whose Q-side operand holds
+// -LSE / scale split into three bf16 terms (exact to 2^-24) and whose K-side operand is ones.
+// Tiles that touch the window or the end of the keys are handled after the pipeline, masked.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
+
+constexpr int kRing = 4;  // tile images per wave
+
+template <int DT, int DH>
+struct Geom {
+  static constexpr int ROW = DH * (DT == CKV_BF16 ? 2 : 4);  // bytes per row
+  static constexpr int CH = ROW / 16;                        // 16-byte chunks per row
+  static constexpr int NCH = CH / 2;                         // chunks per lane (the other half-wave holds the rest)
+  static constexpr int TILE = kTile * ROW;                   // bytes per 32-row tile image
+  static constexpr int NDMA = TILE / 1024;                   // load instructions per tile
+  static constexpr int SW = (CH < 16 ? CH : 16) - 1;         // swizzle mask
+  static_assert(ROW == 128 || ROW == 256, "row size");
+};
+
+// Row and chunk of a tile that lane `lane` moves in load instruction i (the lane's 16 bytes land at
+// image offset 16 * (64 * i + lane)).
+template <class G>
+__device__ __forceinline__ void dma_source(int i, int lane, int &r, int &kappa) {
+  const int s = i * 64 + lane;
+  r = s / G::CH;
+  kappa = (s % G::CH) ^ (r & G::SW);
+}
+
+template <class G>
+__device__ __forceinline__ int image_offset(int r, int kappa) {
+  return r * G::ROW + ((kappa ^ (r & G::SW)) << 4);
+}
+
+// Waits until at most N of this wave's vector memory operations are still in flight (they complete
+// in issue order); also keeps the compiler from moving LDS accesses across the wait.
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");
+}
+
+// Four loads with one M0 write: instruction j reads 16 bytes per lane at sbase + voff_j + 1024 * j
+// and writes them at LDS address lds + 1024 * j + 16 * lane.
+__device__ __forceinline__ void dma_quad(const char *sbase, uint32_t lds, uint32_t v0, uint32_t v1, uint32_t v2,
+                                         uint32_t v3) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+      "global_load_lds_dwordx4 %2, %1 offset:0\n\t"
+      "global_load_lds_dwordx4 %3, %1 offset:1024\n\t"
+      "global_load_lds_dwordx4 %4, %1 offset:2048\n\t"
+      "global_load_lds_dwordx4 %5, %1 offset:3072"
+      :
+      : "s"(lds), "s"(sbase), "v"(v0), "v"(v1), "v"(v2), "v"(v3)
+      : "memory");
+}
+
+// One whole tile whose first row starts at tile_base. voff[i] already holds the lane's source offset
+// minus the immediate of its instruction plus kDmaBias, so the scalar base is tile_base - kDmaBias.
+constexpr int kDmaBias = 3072;
+template <class G>
+__device__ __forceinline__ void dma_tile(const char *tile_base, const uint32_t (&voff)[G::NDMA], uint32_t lds_image) {
+#pragma unroll
+  for (int q = 0; q < G::NDMA / 4; ++q)
+    dma_quad(tile_base - kDmaBias, lds_image + q * 4096, voff[4 * q] + q * 4096, voff[4 * q + 1] + q * 4096,
+             voff[4 * q + 2] + q * 4096, voff[4 * q + 3] + q * 4096);
+}
+
+// A tile whose rows may run past the last key: row indices are clamped (the logits of the clamped
+// rows are masked by the caller). Outside the pipeline, so the plain form will do.
+template <class G>
+__device__ __forceinline__ void dma_tile_clamped(const char *kbase, int64_t ks_t, int t0, int T, int lane,
+                                                 char *image) {
+#pragma unroll
+  for (int i = 0; i < G::NDMA; ++i) {
+    int r, kappa;
+    dma_source<G>(i, lane, r, kappa);
+    const char *src = kbase + (int64_t)min(t0 + r, T - 1) * ks_t + kappa * 16;
+    __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(uintptr_t)(image + i * 1024), 16, 0, 0);
+  }
+}
+
+template <class G>
+__device__ __forceinline__ void read_image(chunk_t (&f)[G::NCH], const char *image, const int (&roff)[G::NCH]) {
+#pragma unroll
+  for (int c = 0; c < G::NCH; ++c) f[c] = *reinterpret_cast<const chunk_t *>(image + roff[c]);
+}
+
+// Scheduling hint for one pipeline step: N_MFMA groups of one MFMA, (where the step also picks up the
+// next key tile) one LDS read, and a few vector instructions.
+template <int N_MFMA, int VALU_PER, int N_DS>
+__device__ __forceinline__ void interleave_hint() {
+#pragma unroll
+  for (int u = 0; u < N_MFMA; ++u) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
+    if (u < N_DS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);          // then a few vector instructions
+  }
+}
+
+// Geometry of a wave's key range: wave-uniform values live in scalar registers.
+struct WaveRange {
+  int wave, t_begin, t_end, n_full;
+};
+__device__ __forceinline__ WaveRange wave_range(const ScoreArgs &a, const BlockCoord &bc) {
+  WaveRange r;
+  r.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  r.t_begin = (bc.chunk * kScoreWaves + r.wave) * a.keys_per_wave;
+  r.t_end = min(r.t_begin + a.keys_per_wave, a.T);
+  r.n_full = max(0, (min(r.t_end, a.P) - r.t_begin) / kTile);  // tiles wholly inside the prefix
+  return r;
+}
+
+// Everything the two staged kernels share: the ring, the per-lane offsets, Q in registers.
+template <int DT, int DH, int NQ>
+struct Staged {
+  using G = Geom<DT, DH>;
+  static constexpr int NCH = G::NCH;
+  typedef char Ring[kScoreWaves][kRing][G::TILE];
+  uint32_t voff[G::NDMA];  // lane's biased source offset inside a K tile, per load instruction
+  int roff[NCH];           // lane's operand chunks inside a tile image
+  const char *kbase;       // first key row of the unit
+  const char *kcur;        // first row of the key tile the pipeline is working on
+  const char *klast;       // first row of the wave's last full tile
+  int64_t tile_stride;
+  uint32_t lds_ring;       // LDS address of this wave's first image
+
+  // Starts the loads of Q (wave w moves query tile w into the last image of its ring) and of the first
+  // three key tiles, then hands every wave all NQ query tiles in registers. jrow[i] = window row of
+  // tile i, row m, or -1 on padding.
+  __device__ __forceinline__ void start(const ScoreArgs &a, const BlockCoord &bc, const WaveRange &wr, Ring &ring,
+                                        int lane, int m, int hh, chunk_t (&qf)[NQ][NCH], int (&jrow)[NQ]) {
+#pragma unroll
+    for (int i = 0; i < G::NDMA; ++i) {
+      int r, kappa;
+      dma_source<G>(i, lane, r, kappa);
+      voff[i] = (uint32_t)(r * a.ks_t + kappa * 16 + kDmaBias - (i % 4) * 1024 - (i / 4) * 4096);
+    }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) roff[c] = image_offset<G>(m, c + NCH * hh);
+    kbase = a.k + bc.b * a.ks_b + bc.g * a.ks_h;
+    kcur = kbase + (int64_t)wr.t_begin * a.ks_t;
+    tile_stride = (int64_t)kTile * a.ks_t;
+    klast = kcur + max(wr.n_full - 1, 0) * tile_stride;
+    lds_ring = (uint32_t)(uintptr_t)&ring[wr.wave][0][0];
+
+    if (wr.wave < NQ) {
+      const int tile = min(bc.grp * NQ + wr.wave, a.n_tiles - 1);
+      const char *qhead = a.q + bc.b * a.qs_b + (bc.g * a.G + tile / a.WT) * a.qs_h;
+      const int j0 = (tile % a.WT) * kTile;
+#pragma unroll
+      for (int i = 0; i < G::NDMA; ++i) {
+        int r, kappa;
+        dma_source<G>(i, lane, r, kappa);
+        const char *src = qhead + (int64_t)min(j0 + r, a.W - 1) * a.qs_w + kappa * 16;
+        __builtin_amdgcn_global_load_lds((glb_void_t *)src,
+                                         (lds_void_t *)(uintptr_t)(ring[wr.wave][kRing - 1] + i * 1024), 16, 0, 0);
+      }
+    }
+    if (wr.n_full > 0) {
+#pragma unroll
+      for (int d = 0; d < kRing - 1; ++d)
+        dma_tile<G>(d < wr.n_full ? kcur + d * tile_stride : klast, voff, lds_ring + d * G::TILE);
+      wait_vm<(kRing - 1) * G::NDMA>();  // Q has landed, the key tiles may still be on their way
+    } else {
+      wait_vm<0>();
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      const int tile = bc.grp * NQ + i;
+      const int j = (tile % a.WT) * kTile + m;
+      const bool valid = tile < a.n_tiles && j < a.W;
+      jrow[i] = valid ? j : -1;
+      read_image<G>(qf[i], ring[i][kRing - 1], roff);
+      if (!valid) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) qf[i][c] = chunk_t{0u, 0u, 0u, 0u};
+      }
+    }
+    __syncthreads();  // the images that held Q are free for key tiles from here on
+  }
+
+  // Load of the tile three ahead of the one at kcur (tile index t + 3) into ring image `slot`; past
+  // the last full tile the last one is fetched again (in bounds, unused).
+  __device__ __forceinline__ void prefetch(int t, int n_full, int slot) {
+    dma_tile<G>(t + 3 < n_full ? kcur + 3 * tile_stride : klast, voff, lds_ring + slot * G::TILE);
+  }
+};
+
+template <int DT, int DH, int NQ>
+__global__ void __launch_bounds__(kScoreWaves *kWave) rowstats_lds_kernel(ScoreArgs a) {
+  using G = Geom<DT, DH>;
+  constexpr int NCH = G::NCH;
+  constexpr int N_MFMA = NCH * (DT == CKV_BF16 ? 1 : 4);
+  constexpr int READ_AT = NQ >= 2 ? NQ - 2 : 0;  // query tile during which the next key tile is picked up
+  __shared__ __attribute__((aligned(1024))) typename Staged<DT, DH, NQ>::Ring ring;
+  const int lane = threadIdx.x & 63, m = lane & 31, hh = lane >> 5;
+  const BlockCoord bc = decode_block(a);
+  const WaveRange wr = wave_range(a, bc);
+
+  Staged<DT, DH, NQ> st;
+  chunk_t qf[NQ][NCH];
+  int jrow[NQ], limit[NQ];
+  st.start(a, bc, wr, ring, lane, m, hh, qf, jrow);
+  float rm[NQ], rl[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    limit[i] = jrow[i] < 0 ? -1 : a.P + jrow[i];  // last key this row may see (causal)
+    rm[i] = -1e30f;
+    rl[i] = 0.0f;
+  }
+
+  chunk_t kreg[2][NCH];
+  f32x16 acc[2];
+  const int n_piped = wr.n_full / kRing * kRing;  // the pipeline takes key tiles one ring at a time
+  if (n_piped > 0) {
+    wait_vm<(kRing - 2) * G::NDMA>();
+    read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
+    mma_chain<DT, NCH>(acc[0], kreg[0], qf[0]);
+  }
+  for (int t0 = 0; t0 < n_piped; t0 += kRing) {
+#pragma unroll
+    for (int u = 0; u < kRing; ++u) {  // tile t0 + u lives in image u and in kreg[u & 1]
+      st.prefetch(t0 + u, wr.n_full, (u + kRing - 1) % kRing);
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        const int cur = (u * NQ + i) & 1;  // accumulator set holding this pair's logits
+        if (i == READ_AT) {
+          wait_vm<(kRing - 2) * G::NDMA>();  // tile t0 + u + 1 has landed
+          read_image<G>(kreg[(u + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
+        }
+        // logits of the next pair; the last pair of a key tile already starts the next key tile
+        if (i + 1 < NQ) mma_chain<DT, NCH>(acc[cur ^ 1], kreg[u & 1], qf[i + 1]);
+        else mma_chain<DT, NCH>(acc[cur ^ 1], kreg[(u + 1) & 1], qf[0]);
+        rowstats_update<false>(acc[cur], a.c2, 0, hh, 0, rm[i], rl[i]);
+        if (i == READ_AT) interleave_hint<N_MFMA, 8, NCH>();
+        else interleave_hint<N_MFMA, 8, 0>();
+      }
+      st.kcur += st.tile_stride;
+    }
+  }
+  wait_vm<0>();
+  for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
+    dma_tile_clamped<G>(st.kbase, a.ks_t, t0, a.T, lane, ring[wr.wave][0]);
+    wait_vm<0>();
+    read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      mma_chain<DT, NCH>(acc[0], kreg[0], qf[i]);
+      rowstats_update<true>(acc[0], a.c2, t0, hh, limit[i], rm[i], rl[i]);
+    }
+  }
+  store_row_partials<NQ>(a, bc, wr.wave, m, hh, rm, rl);
+}
+
+// The extra contraction step of pass 2 that adds bias_j = -LSE_j / scale to every logit of query row
+// j. bf16: the bias as hi + mid + lo bf16 terms in the first three slots of the Q-side operand of the
+// lanes with hh = 0, ones in the same slots on the K side. f32: one 32x32x2 step with (bias, 1).
+__device__ __forceinline__ uint32_t bf16_bits(float x) {  // round to nearest even; x is finite
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+template <int DT>
+struct Bias;
+template <>
+struct Bias<CKV_BF16> {
+  chunk_t q;
+  __device__ __forceinline__ void set(float bias, int hh) {
+    const uint32_t hi = bf16_bits(bias);
+    const float r1 = bias - __uint_as_float(hi << 16);
+    const uint32_t mid = bf16_bits(r1);
+    const float r2 = r1 - __uint_as_float(mid << 16);
+    const uint32_t lo = bf16_bits(r2);
+    q = hh == 0 ? chunk_t{hi | (mid << 16), lo, 0u, 0u} : chunk_t{0u, 0u, 0u, 0u};
+  }
+  static __device__ __forceinline__ chunk_t ones(int hh) {
+    return hh == 0 ? chunk_t{0x3f803f80u, 0x3f80u, 0u, 0u} : chunk_t{0u, 0u, 0u, 0u};
+  }
+  __device__ __forceinline__ void add(f32x16 &acc, const chunk_t &one) const { Mma<CKV_BF16>::step(acc, q, one); }
+};
+template <>
+struct Bias<CKV_F32> {
+  float q;
+  __device__ __forceinline__ void set(float bias, int hh) { q = hh == 0 ? bias : 0.0f; }
+  static __device__ __forceinline__ chunk_t ones(int hh) {
+    return chunk_t{hh == 0 ? 0x3f800000u : 0u, 0u, 0u, 0u};
+  }
+  __device__ __forceinline__ void add(f32x16 &acc, const chunk_t &one) const {
+    const uint32_t o = one[0];
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(q, __uint_as_float(o), acc, 0, 0, 0);
+  }
+};
+
+// Weights exp(z - LSE) of one tile from acc = <q, k> - LSE / scale, summed over this lane's 16 rows.
+template <bool EDGE>
+__device__ __forceinline__ float colsum_weights(const f32x16 &acc, float c2, int hh, int first_masked_row) {
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float pr = __builtin_amdgcn_exp2f(acc[r] * c2);
+    // causal: key kt is visible to window row j iff kt <= P + j, i.e. tile row >= kt - P - j0
+    if (EDGE && acc_row(r, hh) < first_masked_row) pr = 0.0f;
+    s[r & 3] += pr;
+  }
+  return (s[0] + s[1]) + (s[2] + s[3]);
+}
+
+// Adds the two half-waves' row sums and stores one value per (head, key). Heads are taken in pairs:
+// v_permlane32_swap turns (x, y) into ([x.lo, y.lo], [x.hi, y.hi]), so one add leaves head x's
+// totals in lanes 0..31 and head y's in lanes 32..63, and all 64 lanes store.
+// BUFFERED: the store goes through a buffer descriptor that covers the scores of this batch element,
+// and lanes with nothing to store present an offset outside it, which the hardware drops: no branch
+// splits the pipeline's code, and every call issues exactly (NQ / WT + 1) / 2 store instructions.
+template <int NQ, bool BUFFERED>
+__device__ __forceinline__ void store_column_sums(const ScoreArgs &a, const BlockCoord &bc, const float (&cs)[NQ],
+                                                  int WT, int kt, int hh, __amdgpu_buffer_rsrc_t rsrc) {
+  float hv[NQ];  // per head of the group (NQ / WT of them), the sum over its tiles
+  int nh = 0;
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    if (i % WT == 0) hv[nh++] = cs[i];
+    else hv[nh - 1] += cs[i];
+  }
+  const int head0 = bc.g * a.G + (bc.grp * NQ) / WT;  // first head of the group
+  const int heads_left = a.G - (bc.grp * NQ) / WT;    // heads of the KV group from there on
+#pragma unroll
+  for (int h = 0; h < NQ; h += 2) {
+    if (h >= nh) break;
+    const float x = hv[h], y = hv[(h + 1 < nh) ? h + 1 : h];
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    const float tot = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) * a.norm;
+    const int mine = h + hh;  // lanes 32..63 carry the second head of the pair
+    const bool valid = mine < nh && mine < heads_left && kt < a.T;
+    if (BUFFERED) {
+      const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + kt) * 4) : 0x80000000u;
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(tot), rsrc, off, 0, 0);
+    } else if (valid) {
+      a.scores[((size_t)bc.b * a.Hq + head0 + mine) * a.T + kt] = tot;
+    }
+  }
+}
+
+template <int DT, int DH, int NQ, int WT>
+__global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArgs a) {
+  static_assert(NQ % WT == 0, "whole heads");
+  using G = Geom<DT, DH>;
+  constexpr int NCH = G::NCH;
+  constexpr int N_MFMA = NCH * (DT == CKV_BF16 ? 1 : 4) + 1;
+  constexpr int READ_AT = NQ >= 2 ? NQ - 2 : 0;
+  __shared__ __attribute__((aligned(1024))) typename Staged<DT, DH, NQ>::Ring ring;
+  const int lane = threadIdx.x & 63, m = lane & 31, hh = lane >> 5;
+  const BlockCoord bc = decode_block(a);
+  const WaveRange wr = wave_range(a, bc);
+
+  Staged<DT, DH, NQ> st;
+  chunk_t qf[NQ][NCH];
+  int jrow[NQ];
+  st.start(a, bc, wr, ring, lane, m, hh, qf, jrow);
+  // bias of this lane's query row in every tile; padding rows (q = 0) get exp2(-1000) = 0 as weight
+  Bias<DT> bias[NQ];
+  const float to_raw = -kLog2e / a.c2;  // LSE (natural log) -> units of the raw dot product, negated
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int h = bc.g * a.G + (bc.grp * NQ + i) / WT;
+    bias[i].set(jrow[i] >= 0 ? a.lse[((size_t)bc.b * a.Hq + h) * a.W + jrow[i]] * to_raw : -1000.0f / a.c2, hh);
+  }
+  const chunk_t ones = Bias<DT>::ones(hh);
+  // descriptor over scores[b]: Hq * T floats (the host checks that this stays below 2 GiB)
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(a.scores + (size_t)bc.b * a.Hq * a.T), 0, a.Hq * a.T * 4, 0x00020000);
+  // Vector memory operations complete in issue order, stores included. When tile t + 1 is picked up,
+  // the loads of tiles t + 2 and t + 3 and the stores of tiles t - 2 and t - 1 were issued after its
+  // own, so that many operations may still be in flight. Tiles 0 and 1 have no such stores behind
+  // them: dropped stores (offset outside the descriptor) issued after the first loads stand in.
+  constexpr int N_STORES = (NQ / WT + 1) / 2;
+  constexpr int IN_FLIGHT = (kRing - 2) * (G::NDMA + N_STORES);
+#pragma unroll
+  for (int i = 0; i < (kRing - 2) * N_STORES; ++i) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc, 0x80000000u, 0, 0);
+
+  chunk_t kreg[2][NCH];
+  f32x16 acc[2];
+  const int n_piped = wr.n_full / kRing * kRing;
+  if (n_piped > 0) {
+    wait_vm<(kRing - 2) * G::NDMA>();
+    read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
+    mma_chain<DT, NCH>(acc[0], qf[0], kreg[0]);
+    bias[0].add(acc[0], ones);
+  }
+  for (int t0 = 0; t0 < n_piped; t0 += kRing) {
+#pragma unroll
+    for (int u = 0; u < kRing; ++u) {
+      st.prefetch(t0 + u, wr.n_full, (u + kRing - 1) % kRing);
+      float cs[NQ];
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        const int cur = (u * NQ + i) & 1;
+        if (i == READ_AT) {
+          wait_vm<IN_FLIGHT>();  // tile t0 + u + 1 has landed
+          read_image<G>(kreg[(u + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
+        }
+        if (i + 1 < NQ) {
+          mma_chain<DT, NCH>(acc[cur ^ 1], qf[i + 1], kreg[u & 1]);  // rows: query rows, cols: keys
+          bias[i + 1].add(acc[cur ^ 1], ones);
+        } else {
+          mma_chain<DT, NCH>(acc[cur ^ 1], qf[0], kreg[(u + 1) & 1]);
+          bias[0].add(acc[cur ^ 1], ones);
+        }
+        cs[i] = colsum_weights<false>(acc[cur], a.c2, hh, 0);
+        if (i == READ_AT) interleave_hint<N_MFMA, 6, NCH>();
+        else interleave_hint<N_MFMA, 6, 0>();
+      }
+      store_column_sums<NQ, true>(a, bc, cs, WT, wr.t_begin + (t0 + u) * kTile + m, hh, rsrc);
+      st.kcur += st.tile_stride;
+    }
+  }
+  wait_vm<0>();
+  for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
+    dma_tile_clamped<G>(st.kbase, a.ks_t, t0, a.T, lane, ring[wr.wave][0]);
+    wait_vm<0>();
+    read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
+    const int kt = t0 + m;
+    float cs[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      const int j0 = ((bc.grp * NQ + i) % WT) * kTile;
+      mma_chain<DT, NCH>(acc[0], qf[i], kreg[0]);
+      bias[i].add(acc[0], ones);
+      cs[i] = colsum_weights<true>(acc[0], a.c2, hh, kt - a.P - j0);
+    }
+    store_column_sums<NQ, false>(a, bc, cs, WT, kt, hh, rsrc);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Launch
+// ---------------------------------------------------------------------------------------------
+template <int DT, int DH, int NQ>
+static void launch_rowstats(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 block, hipStream_t stream) {
+  if constexpr (DT == CKV_BF16)
+    hipLaunchKernelGGL((rowstats_lds_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
+  else
+    hipLaunchKernelGGL((rowstats_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
+  const int rows = s.Bz * s.Hkv * s.n_groups * NQ * kTile;
+  hipLaunchKernelGGL(lse_kernel<NQ>, dim3((rows + 255) / 256), dim3(256), 0, stream, a, rows);
+}
+
+template <int DT, int DH, int NQ>
+static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 block, hipStream_t stream) {
+  if constexpr (DT == CKV_BF16) {
+    // NQ is a multiple of WT (whole heads per wave)
+    if (s.WT == 1) {
+      hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1>), grid, block, 0, stream, a);
+      return;
+    }
+    if constexpr (NQ % 2 == 0) {
+      if (s.WT == 2) {
+        hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 2>), grid, block, 0, stream, a);
+        return;
+      }
+    }
+    if constexpr (NQ == 3) {
+      if (s.WT == 3) {
+        hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 3>), grid, block, 0, stream, a);
+        return;
+      }
+    }
+    if constexpr (NQ == 4) {
+      if (s.WT == 4) {
+        hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 4>), grid, block, 0, stream, a);
+        return;
+      }
+    }
+  }
+  hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
+}
+
+template <int DT, int DH>
+static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
+                                  hipStream_t stream) {
+  const int units = s.Bz * s.Hkv;
+  const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
+#define CKV_LAUNCH_NQ(NQ)                                                        \
+  case NQ:                                                                       \
+    if (need_lse) launch_rowstats<DT, DH, NQ>(s, a, grid, block, stream);        \
+    if (need_scores) launch_colsum<DT, DH, NQ>(s, a, grid, block, stream);       \
+    break;
+  switch (s.NQ) {
+    CKV_LAUNCH_NQ(1)
+    CKV_LAUNCH_NQ(2)
+    CKV_LAUNCH_NQ(3)
+    CKV_LAUNCH_NQ(4)
+    default: return hipErrorInvalidValue;
+  }
+#undef CKV_LAUNCH_NQ
+  return hipGetLastError();
+}
+
+
+// One definition per (element type, head size), each in a translation unit of its own.
+hipError_t launch_scores_bf16_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
+hipError_t launch_scores_bf16_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
+hipError_t launch_scores_f32_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
+hipError_t launch_scores_f32_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
+
+}  // namespace ckv
+#endif
