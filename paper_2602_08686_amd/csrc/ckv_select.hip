@@ -1,12 +1,16 @@
 // Elastic candidate pool with budget clamp (paper Eq. 8, Alg. 1 Select) as a radix select.
 //
 // One 1024-thread workgroup per (batch, KV head). Utilities are non-negative floats, so their bit
-// patterns order like unsigned integers. The kp-th largest candidate key is found MSB-first, eight
-// bits at a time, with a 256-bin LDS histogram per pass (integer LDS atomics: the counts, and so
-// the result, do not depend on scheduling). The final pass emits the kept positions in ascending
-// order: each wave owns a contiguous range of positions, counts its keepers, and after one scan over
-// the 16 wave totals writes them out with ballot/popcount ranks. Equal keys at the threshold are taken
-// lowest position first, which is exactly "utility descending, position ascending".
+// patterns order like unsigned integers. The kp-th largest candidate key is found MSB-first with an
+// LDS histogram per pass (integer LDS atomics: the counts, and so the result, do not depend on
+// scheduling). The final pass emits the kept positions in ascending order with ranks from prefix
+// counts in position order. Equal keys at the threshold are taken lowest position first, which is
+// exactly "utility descending, position ascending".
+//
+// Two kernels. select_reg_kernel (prefixes of up to 65536 positions, rows 16-byte aligned) reads the
+// utilities once, with 128-bit loads, and keeps them in registers for all passes: digits of 11, 10
+// and 10 bits, so the first one already splits the mantissa and same-address atomics stay rare.
+// select_kernel streams the utilities from L2 in every pass (any length): digits of 8 bits.
 #include "ckv_internal.h"
 
 namespace ckv {
@@ -44,17 +48,18 @@ __device__ __forceinline__ void hist_add(int *hist, bool active, int digit, int 
   if (active) atomicAdd(&hist[digit], 1);
 }
 
-// Executed by wave 0. Scans hist[255..0]; returns through LDS the bin where the running count first
-// reaches k (1-based) and the count strictly above that bin, plus the grand total.
+// Executed by wave 0. Scans hist[NB-1..0]; returns the bin where the running count first reaches k
+// (1-based) and the count strictly above that bin, plus the grand total.
 struct BinResult {
   int bin, above, total;
 };
+template <int NB>
 __device__ __forceinline__ BinResult find_bin(const int *hist, int k, int lane) {
-  // lane i owns bins 255-4i .. 252-4i (descending)
-  int c[4], sum = 0;
+  constexpr int PER = NB / kWave;  // lane i owns bins NB-1-PER*i .. NB-PER*(i+1) (descending)
+  int c[PER], sum = 0;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    c[e] = hist[255 - 4 * lane - e];
+  for (int e = 0; e < PER; ++e) {
+    c[e] = hist[NB - 1 - PER * lane - e];
     sum += c[e];
   }
   int incl = sum;
@@ -71,9 +76,9 @@ __device__ __forceinline__ BinResult find_bin(const int *hist, int k, int lane) 
   if (mine) {
     int run = excl;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < PER; ++e) {
       if (bin < 0 && run + c[e] >= k) {
-        bin = 255 - 4 * lane - e;
+        bin = NB - 1 - PER * lane - e;
         above = run;
       }
       run += c[e];
@@ -87,6 +92,208 @@ __device__ __forceinline__ BinResult find_bin(const int *hist, int k, int lane) 
   return r;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Register-resident select: thread tid holds positions 4 * (j * 1024 + tid) + e, j < NV, e < 4, as
+// keys k' = candidate ? bits + 1 : 0 (so "not a candidate" sorts below every candidate).
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) float f32x4_sel;
+
+// AGGREGATE: lanes that share a digit are counted with one atomic (hist_add). With digits this fine
+// the plain atomics measured faster even in the first pass, where every candidate takes part.
+template <int NV, int SHIFT, int BITS, bool AGGREGATE>
+__device__ __forceinline__ void digit_histogram(int *hist, const uint32_t (&key)[NV][4], uint32_t prefix_hi,
+                                                int lane) {
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t k = key[j][e];
+      const bool active = k != 0u && (k >> (SHIFT + BITS)) == prefix_hi;
+      const int digit = (int)((k >> SHIFT) & ((1u << BITS) - 1u));
+      if (AGGREGATE) hist_add(hist, active, digit, lane);
+      else if (active) atomicAdd(&hist[digit], 1);
+    }
+  }
+}
+
+template <int NV>
+__global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a) {
+  constexpr int NW = kSelectThreads / kWave;
+  __shared__ int hist[2048];
+  __shared__ int wave_tot[NV * NW];  // per (block of 4096 positions, wave): kept-above count | equal count << 16
+  __shared__ int pre_gt[NV * NW + 1], pre_eq[NV * NW + 1];  // their exclusive prefixes, unpacked, then the totals
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_k, s_state;  // s_state: 0 = keep all candidates, 1 = select, 2 = keep none
+
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int P = a.P, W = a.W;
+  const float *u = a.utility + (size_t)unit * P;
+  const float tau = a.tau[unit / a.Hkv];
+  int bud = a.budget[unit];
+  bud = max(W, min(bud, min(a.cap, a.T)));
+  const int kp = bud - W;
+
+  uint32_t key[NV][4];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int t = 4 * (j * kSelectThreads + tid);
+    f32x4_sel x = {-1.0f, -1.0f, -1.0f, -1.0f};
+    if (t < P) x = *reinterpret_cast<const f32x4_sel *>(u + t);  // P % 4 == 0: whole vectors only
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float xe = x[e];
+      key[j][e] = (t < P && xe >= tau) ? key_of(xe) + 1u : 0u;
+    }
+  }
+
+  for (int i = tid; i < 2048; i += kSelectThreads) hist[i] = 0;
+  __syncthreads();
+  digit_histogram<NV, 20, 11, false>(hist, key, 0u, lane);
+  __syncthreads();
+  if (wave == 0) {
+    const BinResult r = find_bin<2048>(hist, max(kp, 1), lane);
+    if (lane == 0) {
+      if (r.total <= kp) s_state = 0;
+      else if (kp == 0) s_state = 2;
+      else {
+        s_state = 1;
+        s_prefix = (uint32_t)r.bin;  // bits 30..20 of the threshold
+        s_k = kp - r.above;          // still needed from inside the chosen bin
+      }
+    }
+  }
+  __syncthreads();
+  const int state = s_state;
+  uint32_t thr = 0u;  // keep-all: every candidate has k' > 0
+  int need_eq = 0;    // how many keys equal to thr are kept
+  if (state == 2) {
+    thr = 0xffffffffu;
+  } else if (state == 1) {
+    {
+      const uint32_t prefix = s_prefix;
+      const int k = s_k;
+      if (tid < 1024) hist[tid] = 0;
+      __syncthreads();
+      digit_histogram<NV, 10, 10, false>(hist, key, prefix, lane);
+      __syncthreads();
+      if (wave == 0) {
+        const BinResult r = find_bin<1024>(hist, k, lane);
+        if (lane == 0) {
+          s_prefix = (prefix << 10) | (uint32_t)r.bin;
+          s_k = k - r.above;
+        }
+      }
+      __syncthreads();
+    }
+    {
+      const uint32_t prefix = s_prefix;
+      const int k = s_k;
+      if (tid < 1024) hist[tid] = 0;
+      __syncthreads();
+      digit_histogram<NV, 0, 10, false>(hist, key, prefix, lane);
+      __syncthreads();
+      if (wave == 0) {
+        const BinResult r = find_bin<1024>(hist, k, lane);
+        if (lane == 0) {
+          s_prefix = (prefix << 10) | (uint32_t)r.bin;
+          s_k = k - r.above;
+        }
+      }
+      __syncthreads();
+    }
+    thr = s_prefix;
+    need_eq = s_k;
+  }
+
+  // Ranks in position order: block j, then wave, then lane, then element. Counts travel packed as
+  // (above | equal << 16); a wave covers 256 positions, so neither half overflows.
+  auto own_count = [&](int j) {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c += (key[j][e] > thr ? 1 : 0) + (key[j][e] == thr ? 0x10000 : 0);
+    return c;
+  };
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int c = own_count(j);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+    if (lane == 0) wave_tot[j * NW + wave] = c;
+  }
+  __syncthreads();
+  // exclusive prefix over the (block, wave) totals in position order, by wave 0; the grand totals
+  // end up behind the last entry
+  if (wave == 0) {
+    constexpr int PER = (NV * NW + kWave - 1) / kWave;
+    int g[PER], q[PER], sg = 0, sq = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int i = lane * PER + e;
+      const int c = i < NV * NW ? wave_tot[i] : 0;
+      g[e] = c & 0xffff;
+      q[e] = c >> 16;
+      sg += g[e];
+      sq += q[e];
+    }
+    int ig = sg, iq = sq;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int ug = __shfl_up(ig, o), uq = __shfl_up(iq, o);
+      if (lane >= o) {
+        ig += ug;
+        iq += uq;
+      }
+    }
+    int rg = ig - sg, rq = iq - sq;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int i = lane * PER + e;
+      if (i < NV * NW) {
+        pre_gt[i] = rg;
+        pre_eq[i] = rq;
+      }
+      rg += g[e];
+      rq += q[e];
+    }
+    if (lane == 63) {
+      pre_gt[NV * NW] = ig;
+      pre_eq[NV * NW] = iq;
+    }
+  }
+  __syncthreads();
+  const int tot_gt = pre_gt[NV * NW], tot_eq = pre_eq[NV * NW];
+  int32_t *out = a.idx + (size_t)unit * a.cap;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int own = own_count(j);
+    int incl = own;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    const int before = incl - own;
+    int gt_before = pre_gt[j * NW + wave] + (before & 0xffff), eq_before = pre_eq[j * NW + wave] + (before >> 16);
+    const int t = 4 * (j * kSelectThreads + tid);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool gt = key[j][e] > thr, eq = key[j][e] == thr;
+      if (gt || (eq && eq_before < need_eq)) {
+        const int pos = gt_before + min(eq_before, need_eq);
+        if (pos < kp) out[pos] = t + e;
+      }
+      gt_before += gt;
+      eq_before += eq;
+    }
+  }
+  const int kept = min(tot_gt + min(tot_eq, need_eq), kp);
+  for (int j = tid; j < W; j += kSelectThreads) out[kept + j] = P + j;
+  if (tid == 0) a.count[unit] = kept + W;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Streaming select: any length.
+// ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   __shared__ int hist[256];
   __shared__ int wave_gt[kSelectThreads / kWave], wave_eq[kSelectThreads / kWave];
@@ -111,7 +318,7 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   }
   __syncthreads();
   if (wave == 0) {
-    const BinResult r = find_bin(hist, max(kp, 1), lane);
+    const BinResult r = find_bin<256>(hist, max(kp, 1), lane);
     if (lane == 0) {
       if (r.total <= kp) s_state = 0;
       else if (kp == 0) s_state = 2;
@@ -145,7 +352,7 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
       }
       __syncthreads();
       if (wave == 0) {
-        const BinResult r = find_bin(hist, k, lane);
+        const BinResult r = find_bin<256>(hist, k, lane);
         if (lane == 0) {
           s_prefix = prefix | ((uint32_t)r.bin << shift);
           s_k = k - r.above;
@@ -230,7 +437,15 @@ hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utili
   a.count = count;
   a.Hkv = s.Hkv; a.T = s.T; a.W = s.W; a.P = s.P;
   a.cap = p->cap;
-  hipLaunchKernelGGL(select_kernel, dim3(s.Bz * s.Hkv), dim3(kSelectThreads), 0, stream, a);
+  const dim3 grid(s.Bz * s.Hkv), block(kSelectThreads);
+  const int vectors = (s.P + 4 * kSelectThreads - 1) / (4 * kSelectThreads);  // 128-bit loads per thread
+  const bool aligned = s.P % 4 == 0 && (uintptr_t)utility % 16 == 0 && s.P > 0;
+  if (aligned && vectors <= 1) hipLaunchKernelGGL(select_reg_kernel<1>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 2) hipLaunchKernelGGL(select_reg_kernel<2>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 4) hipLaunchKernelGGL(select_reg_kernel<4>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 8) hipLaunchKernelGGL(select_reg_kernel<8>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 16) hipLaunchKernelGGL(select_reg_kernel<16>, grid, block, 0, stream, a);
+  else hipLaunchKernelGGL(select_kernel, grid, block, 0, stream, a);
   return hipGetLastError();
 }
 
