@@ -49,6 +49,21 @@ def scan_flops(w) -> float:
     return 2.0 * w.batch * w.n_q_heads * w.window * w.seq_len * w.head_dim
 
 
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` on the C3 workload as measured with rocprofv3 counters
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size): read from the committed summary of
+    those runs, since counters cannot be collected from inside a timing run. None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_c3.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "traffic" and f[1] == "kernel=" + kernel:
+                return int(f[2].split("=")[1]) + int(f[3].split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, layer_t, tables, n_batch: int, value_norm: bool) -> dict:
     """Times the oracle (as it stands) on the first n_batch batch elements of layer 0."""
     import numpy as np
@@ -89,6 +104,8 @@ def main() -> int:
     ap.add_argument("--given-lse", action="store_true", help="caller-supplied LSE: single pass over K")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=0, help="batch elements in the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (a kernel of known traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
@@ -161,12 +178,15 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_pass1 = sum(a.elapsed_time(b_) for a, b_ in pairs1) / len(pairs1)
     ms_pass2 = sum(a.elapsed_time(b_) for a, b_ in pairs2) / len(pairs2)
-    dominant, dom_ms = (("rowstats_kernel", ms_pass1) if ms_pass1 >= ms_pass2 and not args.given_lse
-                        else ("colsum_kernel", ms_pass2))
+    bf16 = w.dtype == "bf16"
+    dominant, dom_ms = ((("rowstats_lds_kernel" if bf16 else "rowstats_kernel"), ms_pass1)
+                        if ms_pass1 >= ms_pass2 and not args.given_lse
+                        else (("colsum_lds_kernel" if bf16 else "colsum_kernel"), ms_pass2))
     achieved = scan_bytes(w) / (dom_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": measured_traffic(dominant) if args.config == "c3" and not args.value_norm else None,
         "ms_per_launch": round(dom_ms, 4),
         "scan_ms": {"rowstats+lse": round(ms_pass1, 4), "colsum": round(ms_pass2, 4)},
         "mfma_tflops": {"rowstats": round(scan_flops(w) / (ms_pass1 * 1e-3) / 1e12, 1),
@@ -174,6 +194,14 @@ def main() -> int:
                         "peak": MFMA_BF16_PEAK_TFLOPS},
         "whole_pass_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
     }
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = {
         "metric": "achieved HBM GB/s (algorithmic bytes / time) of prefill-end scan+select+gather; ms/layer beside it",
