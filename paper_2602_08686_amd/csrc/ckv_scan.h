@@ -671,12 +671,9 @@ __device__ __forceinline__ float colsum_weights(const f32x16 &acc, float c2, int
 // Adds the two half-waves' row sums and stores one value per (head, key). Heads are taken in pairs:
 // v_permlane32_swap turns (x, y) into ([x.lo, y.lo], [x.hi, y.hi]), so one add leaves head x's
 // totals in lanes 0..31 and head y's in lanes 32..63, and all 64 lanes store.
-// BUFFERED: the store goes through a buffer descriptor that covers the scores of this batch element,
-// and lanes with nothing to store present an offset outside it, which the hardware drops: no branch
-// splits the pipeline's code, and every call issues exactly (NQ / WT + 1) / 2 store instructions.
-template <int NQ, bool BUFFERED>
+template <int NQ>
 __device__ __forceinline__ void store_column_sums(const ScoreArgs &a, const BlockCoord &bc, const float (&cs)[NQ],
-                                                  int WT, int kt, int hh, __amdgpu_buffer_rsrc_t rsrc) {
+                                                  int WT, int kt, int hh) {
   float hv[NQ];  // per head of the group (NQ / WT of them), the sum over its tiles
   int nh = 0;
 #pragma unroll
@@ -693,13 +690,47 @@ __device__ __forceinline__ void store_column_sums(const ScoreArgs &a, const Bloc
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
     const float tot = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) * a.norm;
     const int mine = h + hh;  // lanes 32..63 carry the second head of the pair
-    const bool valid = mine < nh && mine < heads_left && kt < a.T;
-    if (BUFFERED) {
-      const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + kt) * 4) : 0x80000000u;
-      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(tot), rsrc, off, 0, 0);
-    } else if (valid) {
-      a.scores[((size_t)bc.b * a.Hq + head0 + mine) * a.T + kt] = tot;
-    }
+    if (mine < nh && mine < heads_left && kt < a.T) a.scores[((size_t)bc.b * a.Hq + head0 + mine) * a.T + kt] = tot;
+  }
+}
+
+// Pipeline form of the same: the totals of one key tile go to a per-wave LDS stage
+// [head of the group][key of the ring cycle], and once per ring cycle (4 tiles, 128 keys) every lane
+// stores four consecutive keys of one head with one 128-bit buffer store per pair of heads.
+template <int NQ, int WT>
+__device__ __forceinline__ void stage_column_sums(const float (&cs)[NQ], float norm, float *stage, int u, int m,
+                                                  int hh) {
+  constexpr int NH = NQ / WT;
+  float hv[NH];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    hv[h] = cs[h * WT];
+#pragma unroll
+    for (int e = 1; e < WT; ++e) hv[h] += cs[h * WT + e];
+  }
+#pragma unroll
+  for (int h = 0; h < NH; h += 2) {
+    const float x = hv[h], y = hv[(h + 1 < NH) ? h + 1 : h];
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    const float tot = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) * norm;
+    if (h + hh < NH) stage[(h + hh) * (kRing * kTile) + u * kTile + m] = tot;
+  }
+}
+
+template <int NQ, int WT>
+__device__ __forceinline__ void flush_column_sums(const ScoreArgs &a, const BlockCoord &bc, const float *stage,
+                                                  int t_first, int lane, __amdgpu_buffer_rsrc_t rsrc) {
+  constexpr int NH = NQ / WT;
+  const int head0 = bc.g * a.G + (bc.grp * NQ) / WT;
+  const int heads_left = a.G - (bc.grp * NQ) / WT;
+#pragma unroll
+  for (int h = 0; h < NH; h += 2) {
+    const int mine = h + (lane >> 5), key4 = 4 * (lane & 31);
+    const bool valid = mine < NH && mine < heads_left;
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(stage + (valid ? mine : 0) * (kRing * kTile) + key4);
+    const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + t_first + key4) * 4) : 0x80000000u;
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, 0);
   }
 }
 
@@ -728,17 +759,21 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
     bias[i].set(jrow[i] >= 0 ? a.lse[((size_t)bc.b * a.Hq + h) * a.W + jrow[i]] * to_raw : -1000.0f / a.c2, hh);
   }
   const chunk_t ones = Bias<DT>::ones(hh);
-  // descriptor over scores[b]: Hq * T floats (the host checks that this stays below 2 GiB)
+  // Descriptor over scores[b]: Hq * T floats (the host checks that this stays below 2 GiB). Lanes with
+  // nothing to store present an offset outside it, which the hardware drops: no branch splits the
+  // pipeline's code, and every flush issues exactly N_STORES store instructions.
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void *)(a.scores + (size_t)bc.b * a.Hq * a.T), 0, a.Hq * a.T * 4, 0x00020000);
   // Vector memory operations complete in issue order, stores included. When tile t + 1 is picked up,
-  // the loads of tiles t + 2 and t + 3 and the stores of tiles t - 2 and t - 1 were issued after its
-  // own, so that many operations may still be in flight. Tiles 0 and 1 have no such stores behind
-  // them: dropped stores (offset outside the descriptor) issued after the first loads stand in.
+  // the loads of tiles t + 2 and t + 3 were issued after its own, and so were the stores of the
+  // previous ring cycle if t is the cycle's first or second tile; that many operations may still be
+  // in flight. The first cycle has no such stores behind it: dropped stores (offset outside the
+  // descriptor) issued after the first loads stand in.
   constexpr int N_STORES = (NQ / WT + 1) / 2;
-  constexpr int IN_FLIGHT = (kRing - 2) * (G::NDMA + N_STORES);
+  __shared__ __attribute__((aligned(16))) float s_stage[kScoreWaves][(NQ / WT) * kRing * kTile];
+  float *stage = s_stage[wr.wave];
 #pragma unroll
-  for (int i = 0; i < (kRing - 2) * N_STORES; ++i) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc, 0x80000000u, 0, 0);
+  for (int i = 0; i < N_STORES; ++i) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc, 0x80000000u, 0, 0);
 
   chunk_t kreg[2][NCH];
   f32x16 acc[2];
@@ -758,7 +793,8 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
       for (int i = 0; i < NQ; ++i) {
         const int cur = (u * NQ + i) & 1;
         if (i == READ_AT) {
-          wait_vm<IN_FLIGHT>();  // tile t0 + u + 1 has landed
+          if (u < 2) wait_vm<(kRing - 2) * G::NDMA + N_STORES>();  // tile t0 + u + 1 has landed
+          else wait_vm<(kRing - 2) * G::NDMA>();
           read_image<G>(kreg[(u + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
         }
         if (i + 1 < NQ) {
@@ -772,9 +808,10 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
         if (i == READ_AT) interleave_hint<N_MFMA, 6, NCH>();
         else interleave_hint<N_MFMA, 6, 0>();
       }
-      store_column_sums<NQ, true>(a, bc, cs, WT, wr.t_begin + (t0 + u) * kTile + m, hh, rsrc);
+      stage_column_sums<NQ, WT>(cs, a.norm, stage, u, m, hh);
       st.kcur += st.tile_stride;
     }
+    flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
   }
   wait_vm<0>();
   for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
@@ -790,7 +827,7 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
       bias[i].add(acc[0], ones);
       cs[i] = colsum_weights<true>(acc[0], a.c2, hh, kt - a.P - j0);
     }
-    store_column_sums<NQ, false>(a, bc, cs, WT, kt, hh, rsrc);
+    store_column_sums<NQ>(a, bc, cs, WT, kt, hh);
   }
 }
 
