@@ -294,6 +294,8 @@ __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a
 // ---------------------------------------------------------------------------------------------
 // Streaming select: any length.
 // ---------------------------------------------------------------------------------------------
+constexpr int kUnroll = 8;
+
 __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   __shared__ int hist[256];
   __shared__ int wave_gt[kSelectThreads / kWave], wave_eq[kSelectThreads / kWave];
@@ -311,10 +313,16 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   // pass 0: histogram of the top byte over the candidates (also counts them)
   if (tid < 256) hist[tid] = 0;
   __syncthreads();
-  for (int t0 = 0; t0 < P; t0 += kSelectThreads) {
-    const int t = t0 + tid;
-    const float x = t < P ? u[t] : -1.0f;
-    hist_add(hist, t < P && x >= tau, (int)(key_of(x) >> 24), lane);
+  // eight loads in flight per thread: the pass is bound by L2 latency, not by arithmetic
+  for (int t0 = 0; t0 < P; t0 += kUnroll * kSelectThreads) {
+    float x[kUnroll];
+#pragma unroll
+    for (int e = 0; e < kUnroll; ++e) {
+      const int t = t0 + e * kSelectThreads + tid;
+      x[e] = t < P ? u[t] : -INFINITY;  // never a candidate
+    }
+#pragma unroll
+    for (int e = 0; e < kUnroll; ++e) hist_add(hist, x[e] >= tau, (int)(key_of(x[e]) >> 24), lane);
   }
   __syncthreads();
   if (wave == 0) {
@@ -344,11 +352,18 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       const uint32_t hi_mask = 0xffffffffu << (shift + 8);
-      for (int t0 = 0; t0 < P; t0 += kSelectThreads) {
-        const int t = t0 + tid;
-        const float x = t < P ? u[t] : -1.0f;
-        const uint32_t key = key_of(x);
-        hist_add(hist, t < P && x >= tau && (key & hi_mask) == prefix, (int)((key >> shift) & 255u), lane);
+      for (int t0 = 0; t0 < P; t0 += kUnroll * kSelectThreads) {
+        float x[kUnroll];
+#pragma unroll
+        for (int e = 0; e < kUnroll; ++e) {
+          const int t = t0 + e * kSelectThreads + tid;
+          x[e] = t < P ? u[t] : -INFINITY;
+        }
+#pragma unroll
+        for (int e = 0; e < kUnroll; ++e) {
+          const uint32_t key = key_of(x[e]);
+          hist_add(hist, x[e] >= tau && (key & hi_mask) == prefix, (int)((key >> shift) & 255u), lane);
+        }
       }
       __syncthreads();
       if (wave == 0) {
@@ -369,18 +384,20 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   const int seg = ((P + n_waves - 1) / n_waves + kWave - 1) / kWave * kWave;
   const int lo = wave * seg, hi = min(lo + seg, P);
   int n_gt = 0, n_eq = 0;
-  for (int t0 = lo; t0 < hi; t0 += kWave) {
-    const int t = t0 + lane;
-    bool gt = false, eq = false;
-    if (t < hi) {
-      const float x = u[t];
-      const uint32_t key = key_of(x);
-      const bool cand = x >= tau;
-      gt = cand && key > thr;
-      eq = cand && key == thr;
+  for (int t0 = lo; t0 < hi; t0 += kUnroll * kWave) {
+    float x[kUnroll];
+#pragma unroll
+    for (int e = 0; e < kUnroll; ++e) {
+      const int t = t0 + e * kWave + lane;
+      x[e] = t < hi ? u[t] : -INFINITY;
     }
-    n_gt += __popcll(__ballot(gt));
-    n_eq += __popcll(__ballot(eq));
+#pragma unroll
+    for (int e = 0; e < kUnroll; ++e) {
+      const uint32_t key = key_of(x[e]);
+      const bool cand = x[e] >= tau;
+      n_gt += __popcll(__ballot(cand && key > thr));
+      n_eq += __popcll(__ballot(cand && key == thr));
+    }
   }
   if (lane == 0) {
     wave_gt[wave] = n_gt;
@@ -394,25 +411,28 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
   }
   int32_t *out = a.idx + (size_t)unit * a.cap;
   const unsigned long long below = (1ull << lane) - 1ull;
-  for (int t0 = lo; t0 < hi; t0 += kWave) {
-    const int t = t0 + lane;
-    bool gt = false, eq = false;
-    if (t < hi) {
-      const float x = u[t];
-      const uint32_t key = key_of(x);
-      const bool cand = x >= tau;
-      gt = cand && key > thr;
-      eq = cand && key == thr;
+  for (int t0 = lo; t0 < hi; t0 += kUnroll * kWave) {
+    float x[kUnroll];
+#pragma unroll
+    for (int e = 0; e < kUnroll; ++e) {
+      const int t = t0 + e * kWave + lane;
+      x[e] = t < hi ? u[t] : -INFINITY;
     }
-    const unsigned long long bg = __ballot(gt), be = __ballot(eq);
-    const int gt_before = base_gt + __popcll(bg & below);
-    const int eq_before = base_eq + __popcll(be & below);
-    if (gt || (eq && eq_before < need_eq)) {
-      const int pos = gt_before + min(eq_before, need_eq);
-      if (pos < kp) out[pos] = t;
+#pragma unroll
+    for (int e = 0; e < kUnroll; ++e) {
+      const uint32_t key = key_of(x[e]);
+      const bool cand = x[e] >= tau;
+      const bool gt = cand && key > thr, eq = cand && key == thr;
+      const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+      const int gt_before = base_gt + __popcll(bg & below);
+      const int eq_before = base_eq + __popcll(be & below);
+      if (gt || (eq && eq_before < need_eq)) {
+        const int pos = gt_before + min(eq_before, need_eq);
+        if (pos < kp) out[pos] = t0 + e * kWave + lane;
+      }
+      base_gt += __popcll(bg);
+      base_eq += __popcll(be);
     }
-    base_gt += __popcll(bg);
-    base_eq += __popcll(be);
   }
   // kept prefix tokens, then the window
   __syncthreads();
