@@ -62,6 +62,36 @@ def test_window_scores_match_oracle(w):
     assert_scores_close(buf.scores.cpu().numpy(), ref, "scores with given LSE")
 
 
+# Long enough, with few enough (batch, KV head) units, that every wave's key range spans whole rounds of
+# the scan kernels' four-tile software pipeline (the cases above mostly take its masked tail path):
+# odd group sizes, several tiles per head, 128-byte rows, ragged ends.
+PIPELINE_CASES = [
+    _small("long_gqa7", "bf16", 1, 7, 1, 128, 70001, 32, pareto_frac=0.05),       # groups of 4 + 3 heads
+    _small("long_gqa3", "bf16", 1, 3, 1, 128, 140003, 32, sink_scale=8.0),        # three tiles per wave
+    _small("long_w64", "bf16", 1, 8, 2, 128, 40000, 64, needles=4),               # two tiles per head
+    _small("long_w128", "bf16", 1, 2, 2, 128, 70000, 128, B_=300),                # four tiles per head
+    _small("long_w48_gqa5", "bf16", 1, 5, 1, 128, 50000, 48),                     # padded second tile, 2+2+1 heads
+    _small("long_d64", "bf16", 1, 4, 2, 64, 70003, 32, head_key_scale=True),      # 128-byte rows
+    _small("long_mha", "bf16", 1, 2, 2, 128, 66000, 32),                          # one tile per wave
+]
+
+
+@pytest.mark.parametrize("w", PIPELINE_CASES, ids=lambda w: w.name)
+def test_window_scores_pipelined_shapes(w):
+    print(f"case {w.name}", flush=True)
+    layer = wl.make_layer(w, 0, DEV)
+    q, k, v = layer["q"], layer["k"], layer["v"]
+    p = params_of(w, q, k, v)
+    buf = B.LayerBuffers(p, DEV)
+    buf.scores.fill_(float("nan"))
+    B.ckv_window_scores(p, q, k, None, None, buf.scores, None, buf.workspace)
+    torch.cuda.synchronize()
+    ref = oracle.window_scores(f32(q), f32(k))
+    got = buf.scores.cpu().numpy()
+    assert_scores_close(got, ref)
+    np.testing.assert_allclose(got.astype(np.float64).sum(-1), w.seq_len, rtol=2e-4)
+
+
 def test_window_scores_strided_inputs():
     # K/V as slices of a fused [Bz, T, Hkv, 2, d] cache, Q as a slice of a longer query tensor
     w = _small("strided", "bf16", 2, 8, 2, 128, 1000, 32)
@@ -97,6 +127,7 @@ CHAIN_CASES = [
     (_small("chain_bf16_max_shares", "bf16", 2, 12, 4, 128, 2222, 64, wl.POOL_MAX, 7, 300, shares=True,
             needles=5, sink_scale=8.0), True),
     (_small("chain_f32_nopool", "f32", 1, 4, 2, 64, 900, 16, wl.POOL_NONE, 1, 100, shares=True), False),
+    (_small("chain_long_gqa7", "bf16", 1, 7, 1, 128, 60004, 32, wl.POOL_AVG, 7, 600, gate=True, needles=6), True),
 ]
 
 
