@@ -47,7 +47,14 @@ typedef enum { CKV_POOL_NONE = 0, CKV_POOL_AVG = 1, CKV_POOL_MAX = 2 } ckv_pool;
 
 /* flags */
 enum {
-  CKV_FLAG_VALUE_NORM = 1u /* multiply the window mass by the value-norm ratio rho (paper Eq. 4)   */
+  CKV_FLAG_VALUE_NORM = 1u, /* multiply the window mass by the value-norm ratio rho (paper Eq. 4)  */
+  /* ckv_window_scores with lse == NULL has two implementations of the same scan (identical
+   * definitions, results equal within rounding): two kernels that stream K twice, and one persistent
+   * kernel that reads K once and keeps a unit's keys on chip between the passes (bf16, G*ceil(W/32)
+   * <= 4). The library picks by shape; these flags force one of them (at most one may be set;
+   * SINGLE_READ is ignored where that kernel does not exist).                                      */
+  CKV_FLAG_SCAN_TWO_KERNELS = 2u,
+  CKV_FLAG_SCAN_SINGLE_READ = 4u
 };
 
 /* Problem description shared by all calls. Plain data; the caller may reuse or free it after a call. */
@@ -104,6 +111,17 @@ size_t ckv_workspace_bytes(const ckv_params *params);
 ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const void *k,
                              const void *v, const float *lse, float *scores, float *vnorm_ratio,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Error word of the single-read scan. That scan (see CKV_FLAG_SCAN_SINGLE_READ) is one persistent
+ * kernel whose workgroups wait for each other; every such wait is bounded, and a wait that expires
+ * (which needs a GPU that cannot keep the whole launch resident) writes a non-zero uint32 at this
+ * byte offset of `workspace` -- the scores of that call are then invalid. The word is zero after any
+ * other ckv_window_scores call that computed LSE itself. A caller that wants to check reads it once
+ * the stream has reached the call. Returns (size_t)-1 if `params` is invalid or that scan does not
+ * exist for the shape (then there is nothing to check).
+ */
+size_t ckv_scan_status_offset(const ckv_params *params);
 
 /*
  * First half of the scan on its own: LSE_j of every window row, as defined above (the softmax

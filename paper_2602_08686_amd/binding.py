@@ -18,8 +18,10 @@ CKV_OK, CKV_EINVAL, CKV_EUNSUPPORTED, CKV_EWORKSPACE, CKV_EHIP = range(5)
 CKV_F32, CKV_BF16 = 0, 1
 POOL_NONE, POOL_AVG, POOL_MAX = 0, 1, 2
 FLAG_VALUE_NORM = 1
+FLAG_SCAN_TWO_KERNELS = 2   # force the scan that streams K twice
+FLAG_SCAN_SINGLE_READ = 4   # force the persistent scan that reads K once (where it exists)
 
-EXPORTS = ("ckv_workspace_bytes", "ckv_window_lse", "ckv_window_scores", "ckv_apply_tables", "ckv_select_topk",
+EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_status_string")
 
 
@@ -55,6 +57,8 @@ def load(path: Optional[Path] = None):
     vp, pp = ctypes.c_void_p, ctypes.POINTER(CkvParams)
     lib.ckv_workspace_bytes.argtypes = [pp]
     lib.ckv_workspace_bytes.restype = ctypes.c_size_t
+    lib.ckv_scan_status_offset.argtypes = [pp]
+    lib.ckv_scan_status_offset.restype = ctypes.c_size_t
     lib.ckv_window_scores.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ckv_window_scores.restype = ctypes.c_int
     lib.ckv_window_lse.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -127,6 +131,12 @@ def _check(status: int, where: str):
 
 def ckv_workspace_bytes(params: CkvParams) -> int:
     return int(load().ckv_workspace_bytes(ctypes.byref(params)))
+
+
+def ckv_scan_status_offset(params: CkvParams) -> int:
+    """Byte offset of the single-read scan's error word in the workspace, or -1 where there is none."""
+    off = int(load().ckv_scan_status_offset(ctypes.byref(params)))
+    return -1 if off == ctypes.c_size_t(-1).value else off
 
 
 def ckv_window_scores(params, q_win, k, v, lse, scores, vnorm_ratio, workspace, stream=None):

@@ -21,7 +21,9 @@ ckv_status validate(const ckv_params *p) {
   if (p->pool != CKV_POOL_NONE && (p->pool_kernel < 1 || p->pool_kernel > 63 || p->pool_kernel % 2 == 0))
     return CKV_EINVAL;
   if (p->budget_per_kv_head < p->window) return CKV_EINVAL;
-  if (p->flags & ~(uint32_t)CKV_FLAG_VALUE_NORM) return CKV_EINVAL;
+  if (p->flags & ~(uint32_t)(CKV_FLAG_VALUE_NORM | CKV_FLAG_SCAN_TWO_KERNELS | CKV_FLAG_SCAN_SINGLE_READ))
+    return CKV_EINVAL;
+  if ((p->flags & CKV_FLAG_SCAN_TWO_KERNELS) && (p->flags & CKV_FLAG_SCAN_SINGLE_READ)) return CKV_EINVAL;
   if (p->head_dim < 1) return CKV_EINVAL;
   const int64_t b_tot = (int64_t)p->budget_per_kv_head * p->n_kv_heads;
   int64_t need = b_tot - (int64_t)(p->n_kv_heads - 1) * p->window;
@@ -78,6 +80,15 @@ void derive(const ckv_params *p, Shape *s) {
   s->keys_per_wave = (int)kpw;
   s->n_chunks = (int)((s->T + kScoreWaves * kpw - 1) / (kScoreWaves * kpw));
   s->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)s->d);
+  // Single-read scan: each unit goes to one XCD (32 CUs, 128 waves) whose waves keep up to 8 key tiles
+  // each between the passes. By default it is used where that capacity holds a whole unit and a wave
+  // has at least one four-tile pipeline round; the flags force either scan.
+  s->fused_ok = p->dtype == CKV_BF16 && s->n_groups == 1 && s->NQ <= kScoreWaves && s->WT <= 2;
+  const int n_key_tiles = (s->T + kTile - 1) / kTile;
+  const int tiles_per_wave = (n_key_tiles + 127) / 128;
+  s->fused = s->fused_ok && tiles_per_wave >= 4 && tiles_per_wave <= 8 && s->Bz * s->Hkv >= 8;
+  if (p->flags & CKV_FLAG_SCAN_SINGLE_READ) s->fused = s->fused_ok;
+  if (p->flags & CKV_FLAG_SCAN_TWO_KERNELS) s->fused = false;
 }
 
 int vnorm_blocks_per_unit(const Shape &s) {
@@ -97,6 +108,12 @@ void layout(const ckv_params *p, const Shape &s, Workspace *w) {
   w->vsum_off = off;
   w->vsum_bytes = (p->flags & CKV_FLAG_VALUE_NORM) ? units * vnorm_blocks_per_unit(s) * sizeof(float) : 0;
   off = align256(off + w->vsum_bytes);
+  w->sync_off = off;
+  w->sync_bytes = s.fused_ok ? kFusedSyncBytes : 0;
+  off = align256(off + w->sync_bytes);
+  w->fpart_off = off;
+  w->fpart_bytes = s.fused_ok ? (size_t)2 * kFusedGridMax * s.NQ * kTile * sizeof(float2) : 0;
+  off = align256(off + w->fpart_bytes);
   w->total = off;
 }
 
@@ -116,6 +133,15 @@ extern "C" size_t ckv_workspace_bytes(const ckv_params *params) {
   derive(params, &s);
   layout(params, s, &w);
   return w.total;
+}
+
+extern "C" size_t ckv_scan_status_offset(const ckv_params *params) {
+  if (validate(params) != CKV_OK) return (size_t)-1;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  return s.fused_ok ? w.sync_off + sizeof(uint32_t) : (size_t)-1;  // sync word 1
 }
 
 extern "C" ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const void *k,

@@ -31,6 +31,8 @@ struct Shape {
   int keys_per_wave;
   int n_chunks;     // workgroups along the key axis per (unit, group)
   float scale;      // softmax scale
+  bool fused_ok;    // the single-read scan kernel exists for this shape (bf16, one query-tile group)
+  bool fused;       // ... and is the one ckv_window_scores uses when it computes LSE itself
 };
 
 ckv_status validate(const ckv_params *p);
@@ -41,10 +43,21 @@ struct Workspace {
   size_t part_off, part_bytes;   // float2 [units][n_tiles*32][n_chunks] row-stat partials
   size_t lse_off, lse_bytes;     // float  [Bz][Hq][W]
   size_t vsum_off, vsum_bytes;   // float  [units][vnorm blocks] partial sums of value norms
+  size_t sync_off, sync_bytes;   // uint32 synchronisation words of the single-read scan
+  size_t fpart_off, fpart_bytes; // float2 [2][workgroups][NQ*32] row partials of the single-read scan
   size_t total;
 };
 void layout(const ckv_params *p, const Shape &s, Workspace *w);
 int vnorm_blocks_per_unit(const Shape &s);
+
+// Where the single-read scan keeps its synchronisation words and row partials, and its grid.
+struct FusedLaunch {
+  uint32_t *sync;
+  float2 *fpart;
+  int grid;
+};
+constexpr int kFusedGridMax = 1024;   // workgroups the partial buffer is sized for
+constexpr int kFusedSyncBytes = 256;
 
 // Kernel launchers (each returns hipGetLastError() after its launches).
 // lse_in == nullptr: pass 1 first, LSE into lse_out (or the workspace). scores == nullptr: pass 1 only.

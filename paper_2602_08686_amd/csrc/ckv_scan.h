@@ -20,6 +20,8 @@
 // whose workloads are small), and LDS-staged, software-pipelined ones for bf16.
 #ifndef CKV_SCAN_H_
 #define CKV_SCAN_H_
+#include <stdlib.h>
+
 #include "ckv_internal.h"
 
 namespace ckv {
@@ -831,6 +833,10 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
   }
 }
 
+}  // namespace ckv
+#include "ckv_scan_fused.h"
+namespace ckv {
+
 // ---------------------------------------------------------------------------------------------
 // Launch
 // ---------------------------------------------------------------------------------------------
@@ -874,9 +880,56 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
   hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
 }
 
+// Fused single-read scan (bf16, all query tiles in one wave): one cooperative launch of one workgroup
+// per CU after a tiny kernel that clears the synchronisation words. Returns hipErrorNotSupported when
+// no instantiation fits, so the caller can fall back to the two-kernel scan.
+template <int DT, int DH, int NQ>
+static hipError_t launch_fused(const Shape &s, const ScoreArgs &a, const FusedLaunch &fl, hipStream_t stream) {
+  if constexpr (DT != CKV_BF16) {
+    return hipErrorNotSupported;
+  } else {
+    // query tiles per phase: two for the four-tile groups, else one head
+    const void *kernel = nullptr;
+    if constexpr (NQ == 4) {
+      if (s.WT == 1) kernel = getenv("CKV_FUSED_QPH2") ? (const void *)fused_scan_kernel<DT, DH, 4, 1, 2>
+                                                       : (const void *)fused_scan_kernel<DT, DH, 4, 1, 1>;
+      if (s.WT == 2) kernel = (const void *)fused_scan_kernel<DT, DH, 4, 2, 2>;
+    } else if constexpr (NQ == 3) {
+      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 3, 1, 1>;
+    } else if constexpr (NQ == 2) {
+      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 2, 1, 1>;
+      if (s.WT == 2) kernel = (const void *)fused_scan_kernel<DT, DH, 2, 2, 2>;
+    } else {
+      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 1, 1, 1>;
+    }
+    if (!kernel) return hipErrorNotSupported;
+    hipLaunchKernelGGL(fused_init_kernel, dim3(1), dim3(kFusedSyncWords), 0, stream, fl.sync);
+    ScoreArgs ka = a;
+    FusedArgs fa;
+    fa.sync = fl.sync;
+    fa.fpart = fl.fpart;
+    fa.units = s.Bz * s.Hkv;
+    void *params[] = {&ka, &fa};
+    if (getenv("CKV_FUSED_PLAIN_LAUNCH")) return hipLaunchKernel(kernel, dim3(fl.grid), dim3(kScoreWaves * kWave), params, 0, stream);
+    return hipLaunchCooperativeKernel(kernel, dim3(fl.grid), dim3(kScoreWaves * kWave), params, 0, stream);
+  }
+}
+
 template <int DT, int DH>
 static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                  hipStream_t stream) {
+                                  const FusedLaunch *fl, hipStream_t stream) {
+  if (fl && need_lse && need_scores) {
+    hipError_t e = hipErrorNotSupported;
+    switch (s.NQ) {
+      case 1: e = launch_fused<DT, DH, 1>(s, a, *fl, stream); break;
+      case 2: e = launch_fused<DT, DH, 2>(s, a, *fl, stream); break;
+      case 3: e = launch_fused<DT, DH, 3>(s, a, *fl, stream); break;
+      case 4: e = launch_fused<DT, DH, 4>(s, a, *fl, stream); break;
+      default: break;
+    }
+    if (e == hipSuccess) return hipGetLastError();
+    (void)hipGetLastError();  // refused (no instantiation, or the cooperative launch does not fit): two-kernel scan
+  }
   const int units = s.Bz * s.Hkv;
   const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
 #define CKV_LAUNCH_NQ(NQ)                                                        \
@@ -897,10 +950,14 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, b
 
 
 // One definition per (element type, head size), each in a translation unit of its own.
-hipError_t launch_scores_bf16_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
-hipError_t launch_scores_bf16_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
-hipError_t launch_scores_f32_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
-hipError_t launch_scores_f32_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream);
+hipError_t launch_scores_bf16_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
+                                   const FusedLaunch *fl, hipStream_t stream);
+hipError_t launch_scores_bf16_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
+                                   const FusedLaunch *fl, hipStream_t stream);
+hipError_t launch_scores_f32_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
+                                   const FusedLaunch *fl, hipStream_t stream);
+hipError_t launch_scores_f32_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
+                                   const FusedLaunch *fl, hipStream_t stream);
 
 }  // namespace ckv
 #endif
