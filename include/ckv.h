@@ -49,10 +49,11 @@ typedef enum { CKV_POOL_NONE = 0, CKV_POOL_AVG = 1, CKV_POOL_MAX = 2 } ckv_pool;
 enum {
   CKV_FLAG_VALUE_NORM = 1u, /* multiply the window mass by the value-norm ratio rho (paper Eq. 4)  */
   /* ckv_window_scores with lse == NULL has two implementations of the same scan (identical
-   * definitions, results equal within rounding): two kernels that stream K twice, and one persistent
-   * kernel that reads K once and keeps a unit's keys on chip between the passes (bf16, G*ceil(W/32)
-   * <= 4). The library picks by shape; these flags force one of them (at most one may be set;
-   * SINGLE_READ is ignored where that kernel does not exist).                                      */
+   * definitions, results equal within rounding): two kernels that stream K twice (the default), and
+   * one persistent kernel that reads K once and keeps a unit's keys on chip between the passes
+   * (bf16, G*ceil(W/32) <= 4, W <= 64; cooperative launch). SINGLE_READ asks for the latter and is
+   * ignored where it does not exist; TWO_KERNELS names the default explicitly. At most one may be
+   * set.                                                                                            */
   CKV_FLAG_SCAN_TWO_KERNELS = 2u,
   CKV_FLAG_SCAN_SINGLE_READ = 4u
 };
@@ -116,9 +117,9 @@ ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const 
  * Error word of the single-read scan. That scan (see CKV_FLAG_SCAN_SINGLE_READ) is one persistent
  * kernel whose workgroups wait for each other; every such wait is bounded, and a wait that expires
  * (which needs a GPU that cannot keep the whole launch resident) writes a non-zero uint32 at this
- * byte offset of `workspace` -- the scores of that call are then invalid. The word is zero after any
- * other ckv_window_scores call that computed LSE itself. A caller that wants to check reads it once
- * the stream has reached the call. Returns (size_t)-1 if `params` is invalid or that scan does not
+ * byte offset of `workspace` -- the scores of that call are then invalid; otherwise that call leaves
+ * the word zero. Calls that use the two-kernel scan do not touch it. A caller that wants to check
+ * reads it once the stream has reached the call. Returns (size_t)-1 if `params` is invalid or that scan does not
  * exist for the shape (then there is nothing to check).
  */
 size_t ckv_scan_status_offset(const ckv_params *params);

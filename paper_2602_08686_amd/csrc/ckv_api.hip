@@ -80,15 +80,11 @@ void derive(const ckv_params *p, Shape *s) {
   s->keys_per_wave = (int)kpw;
   s->n_chunks = (int)((s->T + kScoreWaves * kpw - 1) / (kScoreWaves * kpw));
   s->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)s->d);
-  // Single-read scan: each unit goes to one XCD (32 CUs, 128 waves) whose waves keep up to 8 key tiles
-  // each between the passes. By default it is used where that capacity holds a whole unit and a wave
-  // has at least one four-tile pipeline round; the flags force either scan.
+  // Single-read scan (bf16, one query-tile group, W <= 64): exists beside the two-kernel scan and is used
+  // only on request. Measured on the 32k / batch-16 GQA shape it is the slower of the two (its team
+  // exchanges and its one-wave-per-SIMD pipelines cost more than the second read of K saves).
   s->fused_ok = p->dtype == CKV_BF16 && s->n_groups == 1 && s->NQ <= kScoreWaves && s->WT <= 2;
-  const int n_key_tiles = (s->T + kTile - 1) / kTile;
-  const int tiles_per_wave = (n_key_tiles + 127) / 128;
-  s->fused = s->fused_ok && tiles_per_wave >= 4 && tiles_per_wave <= 8 && s->Bz * s->Hkv >= 8;
-  if (p->flags & CKV_FLAG_SCAN_SINGLE_READ) s->fused = s->fused_ok;
-  if (p->flags & CKV_FLAG_SCAN_TWO_KERNELS) s->fused = false;
+  s->fused = s->fused_ok && (p->flags & CKV_FLAG_SCAN_SINGLE_READ) != 0;
 }
 
 int vnorm_blocks_per_unit(const Shape &s) {
