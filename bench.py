@@ -102,6 +102,11 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffers (0 = the config's depth)")
     ap.add_argument("--value-norm", action="store_true")
     ap.add_argument("--given-lse", action="store_true", help="caller-supplied LSE: single pass over K")
+    ap.add_argument("--scan", default="two_kernels", choices=["two_kernels", "single_read"],
+                    help="which implementation of the scan ckv_window_scores uses when it computes LSE itself")
+    ap.add_argument("--unfused", action="store_true",
+                    help="ckv_window_scores + ckv_apply_tables instead of ckv_window_utility (materialises the "
+                         "per-head window mass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=0, help="batch elements in the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -126,6 +131,7 @@ def main() -> int:
     w = {c.name[:2]: c for c in wl.CONFIGS}[args.config]
     n_layers = args.layers or w.n_layers
     flags = B.FLAG_VALUE_NORM if args.value_norm else 0
+    flags |= B.FLAG_SCAN_SINGLE_READ if args.scan == "single_read" else B.FLAG_SCAN_TWO_KERNELS
 
     tables = wl.make_tables(w, dev)
     layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
@@ -143,7 +149,8 @@ def main() -> int:
     def step():
         for l in range(n_layers):
             t = layers[l]
-            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, buf, lse=None if lse is None else lse[l])
+            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, buf, lse=None if lse is None else lse[l],
+                              fused_utility=not args.unfused)
 
     for _ in range(args.warmup):
         step()
@@ -171,7 +178,13 @@ def main() -> int:
             a.record()
             B.ckv_window_lse(params[l], t["q"], t["k"], lse_buf, buf.workspace)
             b_.record()
-            B.ckv_window_scores(params[l], t["q"], t["k"], None, lse_buf, buf.scores, None, buf.workspace)
+            if args.unfused:
+                B.ckv_window_scores(params[l], t["q"], t["k"], None, lse_buf, buf.scores, None, buf.workspace)
+            else:  # second pass with pooling, weights and group maximum on chip, plus its edge fix-up kernel
+                B.ckv_window_utility(params[l], t["q"], t["k"], t["v"] if args.value_norm else None, lse_buf,
+                                     tables["w_head"], tables.get("head_share"), tables.get("t_gate"),
+                                     tables.get("n_ent", 0), tables.get("n_ppl", 0), tables.get("risk_bins"),
+                                     buf.scores, buf.vnorm_ratio, buf.utility, buf.budget, buf.tau, buf.workspace)
             c.record()
             pairs1.append((a, b_))
             pairs2.append((b_, c))
@@ -182,15 +195,32 @@ def main() -> int:
     dominant, dom_ms = ((("rowstats_lds_kernel" if bf16 else "rowstats_kernel"), ms_pass1)
                         if ms_pass1 >= ms_pass2 and not args.given_lse
                         else (("colsum_lds_kernel" if bf16 else "colsum_kernel"), ms_pass2))
+    scan_ms = {"rowstats+lse": round(ms_pass1, 4),
+               ("colsum" if args.unfused else "colsum+tables"): round(ms_pass2, 4)}
+    if args.scan == "single_read" and not args.given_lse:
+        # the persistent kernel does both passes in one launch: time the call as a whole
+        whole = []
+        for _ in range(reps):
+            for l in range(n_layers):
+                t = layers[l]
+                a, b_ = ev(), ev()
+                a.record()
+                B.ckv_window_scores(params[l], t["q"], t["k"], None, None, buf.scores, None, buf.workspace)
+                b_.record()
+                whole.append((a, b_))
+        torch.cuda.synchronize()
+        dom_ms = sum(a.elapsed_time(b_) for a, b_ in whole) / len(whole)
+        dominant = "fused_scan_kernel"
+        scan_ms["single_read"] = round(dom_ms, 4)
     achieved = scan_bytes(w) / (dom_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": measured_traffic(dominant) if args.config == "c3" and not args.value_norm else None,
         "ms_per_launch": round(dom_ms, 4),
-        "scan_ms": {"rowstats+lse": round(ms_pass1, 4), "colsum": round(ms_pass2, 4)},
+        "scan_ms": scan_ms,
         "mfma_tflops": {"rowstats": round(scan_flops(w) / (ms_pass1 * 1e-3) / 1e12, 1),
-                        "colsum": round(scan_flops(w) / (ms_pass2 * 1e-3) / 1e12, 1),
+                        "colsum": round(scan_flops(w) / (ms_pass2 * 1e-3) / 1e12, 1),  # fused: its fix-up kernel included
                         "peak": MFMA_BF16_PEAK_TFLOPS},
         "whole_pass_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
     }
@@ -212,7 +242,8 @@ def main() -> int:
         "config": {"workload": w.name, "layers_per_step": n_layers, "batch": w.batch, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.seq_len, "window": w.window,
                    "budget_per_kv_head": w.budget, "pool": ["none", "avg", "max"][w.pool] + str(w.pool_kernel),
-                   "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed",
+                   "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed", "scan": args.scan,
+                   "calls": ("window_scores+apply_tables" if args.unfused else "window_utility") + "+select_topk+compact_kv",
                    "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
         "roofline": roofline,
     }

@@ -169,6 +169,29 @@ ckv_status ckv_apply_tables(const ckv_params *params, const float *scores, const
                             int32_t *budget, float *tau, void *hip_stream);
 
 /*
+ * ckv_window_scores followed by ckv_apply_tables as ONE call that does not materialise the per-head
+ * window mass: same definitions, same utility / budget / tau (within fp32 rounding of the pooled sum),
+ * for callers that only need what the selection consumes (paper Alg. 1 from the window scan up to the
+ * threshold). Where the shape allows it (bf16, W <= 32, G*ceil(W/32) <= 4, pooling kernel <= 7, no
+ * value norm, T and P multiples of four) the scan's second pass pools, weights and maximises over the
+ * group's heads on chip and writes [Bz,Hkv,P] instead of [Bz,Hq,T]; otherwise the two steps run one
+ * after the other through `scores_scratch`.
+ *
+ *   q_win, k, v, lse                                   as for ckv_window_scores
+ *   w_head, head_share, t_gate, n_ent, n_ppl, risk_bins as for ckv_apply_tables
+ *   scores_scratch  scratch  [Bz,Hq,T] fp32; contents undefined on return (the fused pass leaves raw
+ *                            column sums in parts of it only)
+ *   vnorm_ratio     out      as for ckv_window_scores (required with CKV_FLAG_VALUE_NORM, else ignored)
+ *   utility, budget, tau  out  as for ckv_apply_tables
+ *   workspace                ckv_workspace_bytes(params) bytes
+ */
+ckv_status ckv_window_utility(const ckv_params *params, const void *q_win, const void *k, const void *v,
+                              const float *lse, const float *w_head, const float *head_share,
+                              const float *t_gate, int32_t n_ent, int32_t n_ppl, const int32_t *risk_bins,
+                              float *scores_scratch, float *vnorm_ratio, float *utility, int32_t *budget,
+                              float *tau, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Elastic candidate pool with budget clamp (paper Eq. 8, Alg. 1 Select), per (b, kv head g):
  *     cand = { t < P : utility[b,g,t] >= tau[b] },  kp = budget[b,g] - W
  *     Sp   = cand                                         if |cand| <= kp

@@ -21,7 +21,7 @@ FLAG_VALUE_NORM = 1
 FLAG_SCAN_TWO_KERNELS = 2   # force the scan that streams K twice
 FLAG_SCAN_SINGLE_READ = 4   # force the persistent scan that reads K once (where it exists)
 
-EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_apply_tables", "ckv_select_topk",
+EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_status_string")
 
 
@@ -63,6 +63,9 @@ def load(path: Optional[Path] = None):
     lib.ckv_window_scores.restype = ctypes.c_int
     lib.ckv_window_lse.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ckv_window_lse.restype = ctypes.c_int
+    lib.ckv_window_utility.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp,
+                                       vp, vp, ctypes.c_size_t, vp]
+    lib.ckv_window_utility.restype = ctypes.c_int
     lib.ckv_apply_tables.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.ckv_apply_tables.restype = ctypes.c_int
     lib.ckv_select_topk.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -160,6 +163,15 @@ def ckv_apply_tables(params, scores, vnorm_ratio, w_head, head_share, t_gate, n_
            "ckv_apply_tables")
 
 
+def ckv_window_utility(params, q_win, k, v, lse, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,
+                       scores_scratch, vnorm_ratio, utility, budget, tau, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().ckv_window_utility(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(v), _ptr(lse), _ptr(w_head),
+                                     _ptr(head_share), _ptr(t_gate), int(n_ent), int(n_ppl), _ptr(risk_bins),
+                                     _ptr(scores_scratch), _ptr(vnorm_ratio), _ptr(utility), _ptr(budget),
+                                     _ptr(tau), _ptr(workspace), nbytes, _stream(stream)), "ckv_window_utility")
+
+
 def ckv_select_topk(params, utility, budget, tau, idx, count, workspace=None, stream=None):
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().ckv_select_topk(ctypes.byref(params), _ptr(utility), _ptr(budget), _ptr(tau), _ptr(idx),
@@ -192,12 +204,20 @@ class LayerBuffers:
         self.workspace = torch.empty(max(ckv_workspace_bytes(params), 256), dtype=torch.uint8, device=device)
 
 
-def retention_layer(params: CkvParams, q, k, v, tables: dict, buf: LayerBuffers, lse=None, stream=None):
-    """Queues the four calls of one layer back-to-back on the stream; returns nothing (outputs in buf)."""
-    ckv_window_scores(params, q, k, v if params.flags & FLAG_VALUE_NORM else None, lse, buf.scores,
-                      buf.vnorm_ratio, buf.workspace, stream)
-    ckv_apply_tables(params, buf.scores, buf.vnorm_ratio, tables["w_head"], tables.get("head_share"),
-                     tables.get("t_gate"), tables.get("n_ent", 0), tables.get("n_ppl", 0),
-                     tables.get("risk_bins"), buf.utility, buf.budget, buf.tau, stream)
+def retention_layer(params: CkvParams, q, k, v, tables: dict, buf: LayerBuffers, lse=None, stream=None,
+                    fused_utility=False):
+    """Queues the calls of one layer back-to-back on the stream; returns nothing (outputs in buf).
+    fused_utility: ckv_window_utility in place of ckv_window_scores + ckv_apply_tables (buf.scores is
+    then scratch)."""
+    vv = v if params.flags & FLAG_VALUE_NORM else None
+    if fused_utility:
+        ckv_window_utility(params, q, k, vv, lse, tables["w_head"], tables.get("head_share"), tables.get("t_gate"),
+                           tables.get("n_ent", 0), tables.get("n_ppl", 0), tables.get("risk_bins"), buf.scores,
+                           buf.vnorm_ratio, buf.utility, buf.budget, buf.tau, buf.workspace, stream)
+    else:
+        ckv_window_scores(params, q, k, vv, lse, buf.scores, buf.vnorm_ratio, buf.workspace, stream)
+        ckv_apply_tables(params, buf.scores, buf.vnorm_ratio, tables["w_head"], tables.get("head_share"),
+                         tables.get("t_gate"), tables.get("n_ent", 0), tables.get("n_ppl", 0),
+                         tables.get("risk_bins"), buf.utility, buf.budget, buf.tau, stream)
     ckv_select_topk(params, buf.utility, buf.budget, buf.tau, buf.idx, buf.count, buf.workspace, stream)
     ckv_compact_kv(params, k, v, buf.idx, buf.count, buf.k_out, buf.v_out, stream)

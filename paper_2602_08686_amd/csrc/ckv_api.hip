@@ -199,6 +199,64 @@ extern "C" ckv_status ckv_apply_tables(const ckv_params *params, const float *sc
   return CKV_OK;
 }
 
+// Whether ckv_window_utility can run its fused second pass for this call (else it runs the two
+// unfused steps through the scratch buffer): the pipelined bf16 kernels with one 32-row tile per head
+// and all query tiles of a group in one wave, pooling kernels of at most 7 taps, no value norm, rows
+// that keep the 128-bit and 64-bit accesses aligned.
+static bool utility_fast_path(const ckv_params *p, const Shape &s, const float *scratch, const float *utility) {
+  const int kernel = p->pool == CKV_POOL_NONE ? 1 : p->pool_kernel;
+  return p->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1 && !(p->flags & CKV_FLAG_VALUE_NORM) &&
+         kernel / 2 <= 3 && s.T % 4 == 0 && s.P % 4 == 0 && s.P > 0 && (uintptr_t)scratch % 16 == 0 &&
+         (uintptr_t)utility % 16 == 0 && (int64_t)s.Hkv * s.P < (1 << 29);
+}
+
+extern "C" ckv_status ckv_window_utility(const ckv_params *params, const void *q_win, const void *k,
+                                         const void *v, const float *lse, const float *w_head,
+                                         const float *head_share, const float *t_gate, int32_t n_ent,
+                                         int32_t n_ppl, const int32_t *risk_bins, float *scores_scratch,
+                                         float *vnorm_ratio, float *utility, int32_t *budget, float *tau,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!q_win || !k || !scores_scratch || !w_head || !utility || !budget || !tau) return CKV_EINVAL;
+  const bool vn = params->flags & CKV_FLAG_VALUE_NORM;
+  if (vn && (!v || !vnorm_ratio)) return CKV_EINVAL;
+  if (t_gate && (n_ent < 1 || n_ppl < 1 || !risk_bins)) return CKV_EINVAL;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  st = workspace_ok(w, workspace, workspace_bytes);
+  if (st != CKV_OK) return st;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (utility_fast_path(params, s, scores_scratch, utility)) {
+    UtilityFusion fuse;
+    fuse.w_row = w_head + (size_t)params->layer * s.Hq;
+    fuse.utility = utility;
+    fuse.pool = params->pool;
+    const int kernel = params->pool == CKV_POOL_NONE ? 1 : params->pool_kernel;
+    fuse.radius = kernel / 2;
+    fuse.inv_kernel = 1.0f / (float)kernel;
+    Shape s2 = s;
+    s2.fused = false;  // the fused pass belongs to the two-kernel scan
+    if (launch_window_scores(params, s2, w, q_win, k, lse, nullptr, scores_scratch, (char *)workspace, stream,
+                             &fuse) != hipSuccess)
+      return CKV_EHIP;
+    if (launch_utility_fixup(params, s2, scores_scratch, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,
+                             utility, budget, tau, stream) != hipSuccess)
+      return CKV_EHIP;
+    return CKV_OK;
+  }
+  if (launch_window_scores(params, s, w, q_win, k, lse, nullptr, scores_scratch, (char *)workspace, stream) !=
+      hipSuccess)
+    return CKV_EHIP;
+  if (vn && launch_value_norm(params, s, w, v, vnorm_ratio, (char *)workspace, stream) != hipSuccess) return CKV_EHIP;
+  if (launch_apply_tables(params, s, scores_scratch, vnorm_ratio, w_head, head_share, t_gate, n_ent, n_ppl,
+                          risk_bins, utility, budget, tau, stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
 extern "C" ckv_status ckv_select_topk(const ckv_params *params, const float *utility,
                                       const int32_t *budget, const float *tau, int32_t *idx,
                                       int32_t *count, void *workspace, size_t workspace_bytes,

@@ -61,9 +61,22 @@ constexpr int kFusedSyncBytes = 256;
 
 // Kernel launchers (each returns hipGetLastError() after its launches).
 // lse_in == nullptr: pass 1 first, LSE into lse_out (or the workspace). scores == nullptr: pass 1 only.
+// Fused utility form of pass 2 (see ckv_window_utility): where `fuse` is given, the second pass writes
+// utilities of block-interior keys to fuse->utility and raw column sums only where the fix-up kernel
+// needs them (into `scores`).
+struct UtilityFusion {
+  const float *w_row;  // w_head + layer * Hq
+  float *utility;      // [Bz][Hkv][P]
+  int pool, radius;
+  float inv_kernel;
+};
 hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Workspace &w, const void *q,
                                 const void *k, const float *lse_in, float *lse_out, float *scores,
-                                char *ws, hipStream_t stream);
+                                char *ws, hipStream_t stream, const UtilityFusion *fuse = nullptr);
+hipError_t launch_utility_fixup(const ckv_params *p, const Shape &s, const float *sparse_scores,
+                                const float *w_head, const float *head_share, const float *t_gate, int n_ent,
+                                int n_ppl, const int32_t *risk_bins, float *utility, int32_t *budget, float *tau,
+                                hipStream_t stream);
 hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspace &w, const void *v,
                              float *ratio, char *ws, hipStream_t stream);
 hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,

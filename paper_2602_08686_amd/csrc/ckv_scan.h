@@ -20,8 +20,6 @@
 // whose workloads are small), and LDS-staged, software-pipelined ones for bf16.
 #ifndef CKV_SCAN_H_
 #define CKV_SCAN_H_
-#include <stdlib.h>
-
 #include "ckv_internal.h"
 
 namespace ckv {
@@ -43,6 +41,11 @@ struct ScoreArgs {
   const float *lse;  // [Bz][Hq][W] natural log
   float *lse_out;
   float *scores;     // [Bz][Hq][T]
+  // fused utility form of pass 2 only
+  const float *w_row;  // w_head + layer * Hq
+  float *utility;      // [Bz][Hkv][P]
+  int pool, radius;    // pooling mode and radius (kernel / 2, at most kUtilMaxRadius)
+  float inv_kernel;    // 1 / pool_kernel
 };
 
 template <int DT> struct Mma;
@@ -405,15 +408,18 @@ __device__ __forceinline__ void wait_vm() {
 }
 
 // Four loads with one M0 write: instruction j reads 16 bytes per lane at sbase + voff_j + 1024 * j
-// and writes them at LDS address lds + 1024 * j + 16 * lane.
+// and writes them at LDS address lds + 1024 * j + 16 * lane. K is read once per pass and never again
+// before everything else has gone through the caches: the loads are marked non-temporal (streaming),
+// which measurably raises the rate at which HBM delivers them and leaves L2 and the memory-side cache
+// to the data that is reused (Q, the column sums on their way to the next kernel).
 __device__ __forceinline__ void dma_quad(const char *sbase, uint32_t lds, uint32_t v0, uint32_t v1, uint32_t v2,
                                          uint32_t v3) {
   asm volatile(
       "s_mov_b32 m0, %0\n\ts_nop 0\n\t"
-      "global_load_lds_dwordx4 %2, %1 offset:0\n\t"
-      "global_load_lds_dwordx4 %3, %1 offset:1024\n\t"
-      "global_load_lds_dwordx4 %4, %1 offset:2048\n\t"
-      "global_load_lds_dwordx4 %5, %1 offset:3072"
+      "global_load_lds_dwordx4 %2, %1 offset:0 nt\n\t"
+      "global_load_lds_dwordx4 %3, %1 offset:1024 nt\n\t"
+      "global_load_lds_dwordx4 %4, %1 offset:2048 nt\n\t"
+      "global_load_lds_dwordx4 %5, %1 offset:3072 nt"
       :
       : "s"(lds), "s"(sbase), "v"(v0), "v"(v1), "v"(v2), "v"(v3)
       : "memory");
@@ -699,7 +705,7 @@ __device__ __forceinline__ void store_column_sums(const ScoreArgs &a, const Bloc
 // Pipeline form of the same: the totals of one key tile go to a per-wave LDS stage
 // [head of the group][key of the ring cycle], and once per ring cycle (4 tiles, 128 keys) every lane
 // stores four consecutive keys of one head with one 128-bit buffer store per pair of heads.
-template <int NQ, int WT>
+template <int NQ, int WT, int ROW = kRing * kTile>
 __device__ __forceinline__ void stage_column_sums(const float (&cs)[NQ], float norm, float *stage, int u, int m,
                                                   int hh) {
   constexpr int NH = NQ / WT;
@@ -715,7 +721,7 @@ __device__ __forceinline__ void stage_column_sums(const float (&cs)[NQ], float n
     const float x = hv[h], y = hv[(h + 1 < NH) ? h + 1 : h];
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
     const float tot = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) * norm;
-    if (h + hh < NH) stage[(h + hh) * (kRing * kTile) + u * kTile + m] = tot;
+    if (h + hh < NH) stage[(h + hh) * ROW + u * kTile + m] = tot;
   }
 }
 
@@ -736,7 +742,114 @@ __device__ __forceinline__ void flush_column_sums(const ScoreArgs &a, const Bloc
   }
 }
 
-template <int DT, int DH, int NQ, int WT>
+// Fused form of the flush (ckv_window_utility): instead of the column sums, the wave writes the
+// UTILITY -- pooled along the keys, weighted per head, maximum over the group's heads (paper Eq. 6) --
+// straight from the stage. A stage row holds, in front of the block's 128 values, the last eight of
+// the previous block, and each flush covers the 128 keys that END four keys before the block does,
+// so every pooling window (radius <= 3) lies inside the row. What this leaves out per wave range --
+// the first four keys, the last four keys of the pipelined part, and the tail tiles -- a small kernel
+// computes afterwards from raw column sums, which the first block (its first eight keys), the last
+// block (its last eight keys) and the tail tiles store. Lanes 0..31 take the even heads of the group,
+// lanes 32..63 the odd ones, four consecutive keys each (three 128-bit reads per head); the halves
+// then swap so that each lane ends up with the group maximum of two adjacent keys and stores them
+// with one 64-bit store. The taps are combined left to right, as the stand-alone tables kernel does.
+constexpr int kUtilCarry = 8;     // values of the previous block kept in front of a stage row
+constexpr int kUtilRow = kUtilCarry + kRing * kTile;
+constexpr int kUtilMaxRadius = 3; // pooling kernels of up to 7 taps
+template <int NH, int POOL, int R>
+__device__ __forceinline__ void pooled_group_max(const ScoreArgs &a, const float *rows, int lane, int heads_left,
+                                                 const float (&wgt)[NH], float (&best)[4]) {
+  const int half = lane >> 5, grp = lane & 31;  // keys 4 grp - 4 .. 4 grp - 1 of the block
+#pragma unroll
+  for (int e = 0; e < 4; ++e) best[e] = -INFINITY;
+#pragma unroll
+  for (int hp = 0; hp < (NH + 1) / 2; ++hp) {
+    const int h = 2 * hp + half;
+    if (2 * hp >= heads_left) break;
+    const bool live = h < NH && h < heads_left;
+    const float *row = rows + (live ? h : 0) * kUtilRow + 4 * grp;  // row[4 .. 7] are this lane's keys
+    float w[12];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(row + 4 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[4 * q + e] = v[e];
+    }
+    float wg = 0.0f;
+#pragma unroll
+    for (int x = 0; x < NH; ++x) wg = (x == h) ? wgt[x] : wg;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float c = w[4 + e - R];
+#pragma unroll
+      for (int d = 1 - R; d <= R; ++d) c = POOL == CKV_POOL_MAX ? fmaxf(c, w[4 + e + d]) : c + w[4 + e + d];
+      if (POOL == CKV_POOL_AVG) c *= a.inv_kernel;
+      best[e] = live ? fmaxf(best[e], wg * c) : best[e];
+    }
+  }
+}
+
+// rows: the wave's stage rows (carry included); t_first: first key of the block just staged.
+template <int NQ, int WT>
+__device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoord &bc, float *rows, int t_first,
+                                              bool first_block, bool last_block, int lane,
+                                              __amdgpu_buffer_rsrc_t rsrc, __amdgpu_buffer_rsrc_t rsrc_u,
+                                              const float (&wgt)[NQ / WT]) {
+  constexpr int NH = NQ / WT;
+  constexpr int BLK = kRing * kTile;
+  const int head0 = bc.g * a.G + (bc.grp * NQ) / WT;
+  const int heads_left = a.G - (bc.grp * NQ) / WT;
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+  typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  // raw column sums for the fix-up kernel: the first block's first eight keys, the last block's last eight
+#pragma unroll
+  for (int h = 0; h < NH; h += 2) {
+    const int mine = h + (lane >> 5), key4 = 4 * (lane & 31);
+    const bool valid = mine < NH && mine < heads_left &&
+                       ((first_block && key4 < kUtilCarry) || (last_block && key4 >= BLK - kUtilCarry));
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(rows + (mine < NH ? mine : 0) * kUtilRow + kUtilCarry + key4);
+    const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + t_first + key4) * 4) : 0x80000000u;
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, 0);
+  }
+  float best[4];
+  if (a.pool == CKV_POOL_MAX) {
+    switch (a.radius) {
+      case 1: pooled_group_max<NH, CKV_POOL_MAX, 1>(a, rows, lane, heads_left, wgt, best); break;
+      case 2: pooled_group_max<NH, CKV_POOL_MAX, 2>(a, rows, lane, heads_left, wgt, best); break;
+      case 3: pooled_group_max<NH, CKV_POOL_MAX, 3>(a, rows, lane, heads_left, wgt, best); break;
+      default: pooled_group_max<NH, CKV_POOL_MAX, 0>(a, rows, lane, heads_left, wgt, best); break;
+    }
+  } else {
+    switch (a.radius) {
+      case 1: pooled_group_max<NH, CKV_POOL_AVG, 1>(a, rows, lane, heads_left, wgt, best); break;
+      case 2: pooled_group_max<NH, CKV_POOL_AVG, 2>(a, rows, lane, heads_left, wgt, best); break;
+      case 3: pooled_group_max<NH, CKV_POOL_AVG, 3>(a, rows, lane, heads_left, wgt, best); break;
+      default: pooled_group_max<NH, CKV_POOL_AVG, 0>(a, rows, lane, heads_left, wgt, best); break;
+    }
+  }
+  // (x, y) -> ([x.lo, y.lo], [x.hi, y.hi]): lanes 0..31 get both halves' values of keys 0 and 1 of their
+  // group, lanes 32..63 those of keys 2 and 3
+  const auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(best[0]), __float_as_uint(best[2]), false, false);
+  const auto s13 = __builtin_amdgcn_permlane32_swap(__float_as_uint(best[1]), __float_as_uint(best[3]), false, false);
+  const f32x2 out = {fmaxf(__uint_as_float(s02[0]), __uint_as_float(s02[1])),
+                     fmaxf(__uint_as_float(s13[0]), __uint_as_float(s13[1]))};
+  const int grp = lane & 31;
+  // group 0 lies in front of the block; in the range's first block it and group 1 (the range's first
+  // four keys, whose windows reach in front of the range) are left to the fix-up kernel
+  const bool emit = grp >= 2 || !first_block;
+  const uint32_t off_u =
+      emit ? (uint32_t)((bc.g * a.P + t_first - 4 + 4 * grp + 2 * (lane >> 5)) * 4) : 0x80000000u;
+  __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, out), rsrc_u, off_u, 0, 0);
+  // carry: the block's last eight values move in front of the rows for the next block
+  if (lane < 2 * NH) {
+    float *row = rows + (lane >> 1) * kUtilRow;
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(row + kUtilCarry + BLK - kUtilCarry + 4 * (lane & 1));
+    *reinterpret_cast<f32x4 *>(row + 4 * (lane & 1)) = v;
+  }
+}
+
+template <int DT, int DH, int NQ, int WT, bool UTIL = false>
 __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArgs a) {
   static_assert(NQ % WT == 0, "whole heads");
   using G = Geom<DT, DH>;
@@ -771,8 +884,17 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
   // previous ring cycle if t is the cycle's first or second tile; that many operations may still be
   // in flight. The first cycle has no such stores behind it: dropped stores (offset outside the
   // descriptor) issued after the first loads stand in.
-  constexpr int N_STORES = (NQ / WT + 1) / 2;
-  __shared__ __attribute__((aligned(16))) float s_stage[kScoreWaves][(NQ / WT) * kRing * kTile];
+  constexpr int N_STORES = (NQ / WT + 1) / 2 + (UTIL ? 1 : 0);  // per flush; the fused form adds the utility store
+  __shared__ __attribute__((aligned(16))) float s_stage[kScoreWaves][(NQ / WT) * (UTIL ? kUtilRow : kRing * kTile)];
+  // fused form: descriptor over utility[b] (Hkv * P floats) and the weights of this group's heads
+  const __amdgpu_buffer_rsrc_t rsrc_u = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(UTIL ? a.utility + (size_t)bc.b * a.Hkv * a.P : a.scores), 0, UTIL ? a.Hkv * a.P * 4 : 0, 0x00020000);
+  float wgt[NQ / WT];
+#pragma unroll
+  for (int h = 0; h < NQ / WT; ++h) {
+    const int head = bc.g * a.G + (bc.grp * NQ) / WT + h;
+    wgt[h] = UTIL && head < a.Hq ? a.w_row[head] : 0.0f;
+  }
   float *stage = s_stage[wr.wave];
 #pragma unroll
   for (int i = 0; i < N_STORES; ++i) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc, 0x80000000u, 0, 0);
@@ -810,10 +932,13 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
         if (i == READ_AT) interleave_hint<N_MFMA, 6, NCH>();
         else interleave_hint<N_MFMA, 6, 0>();
       }
-      stage_column_sums<NQ, WT>(cs, a.norm, stage, u, m, hh);
+      if constexpr (UTIL) stage_column_sums<NQ, WT, kUtilRow>(cs, a.norm, stage + kUtilCarry, u, m, hh);
+      else stage_column_sums<NQ, WT>(cs, a.norm, stage, u, m, hh);
       st.kcur += st.tile_stride;
     }
-    flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
+    if constexpr (UTIL)
+      flush_utility<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, t0 == 0, t0 + kRing >= n_piped, lane, rsrc, rsrc_u, wgt);
+    else flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
   }
   wait_vm<0>();
   for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
@@ -855,7 +980,8 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
   if constexpr (DT == CKV_BF16) {
     // NQ is a multiple of WT (whole heads per wave)
     if (s.WT == 1) {
-      hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1>), grid, block, 0, stream, a);
+      if (a.utility) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1>), grid, block, 0, stream, a);
       return;
     }
     if constexpr (NQ % 2 == 0) {
@@ -891,8 +1017,7 @@ static hipError_t launch_fused(const Shape &s, const ScoreArgs &a, const FusedLa
     // query tiles per phase: two for the four-tile groups, else one head
     const void *kernel = nullptr;
     if constexpr (NQ == 4) {
-      if (s.WT == 1) kernel = getenv("CKV_FUSED_QPH2") ? (const void *)fused_scan_kernel<DT, DH, 4, 1, 2>
-                                                       : (const void *)fused_scan_kernel<DT, DH, 4, 1, 1>;
+      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 4, 1, 1>;  // 64 more registers for Q would spill
       if (s.WT == 2) kernel = (const void *)fused_scan_kernel<DT, DH, 4, 2, 2>;
     } else if constexpr (NQ == 3) {
       if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 3, 1, 1>;
@@ -910,7 +1035,6 @@ static hipError_t launch_fused(const Shape &s, const ScoreArgs &a, const FusedLa
     fa.fpart = fl.fpart;
     fa.units = s.Bz * s.Hkv;
     void *params[] = {&ka, &fa};
-    if (getenv("CKV_FUSED_PLAIN_LAUNCH")) return hipLaunchKernel(kernel, dim3(fl.grid), dim3(kScoreWaves * kWave), params, 0, stream);
     return hipLaunchCooperativeKernel(kernel, dim3(fl.grid), dim3(kScoreWaves * kWave), params, 0, stream);
   }
 }

@@ -46,9 +46,11 @@ struct FusedArgs {
   int units;       // Bz * Hkv
 };
 
-static inline __global__ void fused_init_kernel(uint32_t *sync) {
+namespace {  // one copy per translation unit that includes this header
+__global__ void __attribute__((unused)) fused_init_kernel(uint32_t *sync) {
   if (threadIdx.x < kFusedSyncWords) sync[threadIdx.x] = 0u;
 }
+}  // namespace
 
 __device__ __forceinline__ uint32_t load_dev(const uint32_t *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -124,12 +126,6 @@ __device__ __forceinline__ void read_lds(chunk_t (&f)[NCH], const uint32_t (&vad
   for (int c = 0; c < NCH; ++c)
     f[c] = *(const __attribute__((address_space(3))) chunk_t *)(uintptr_t)(vaddr[c] + (uint32_t)delta);
 }
-
-#ifdef CKV_FUSED_TIMING
-#define CKV_STAMP(i) do { if (k == 1 && xcc == 0 && rank == 0 && tid == 0) ((unsigned long long *)(f.sync + 48))[i] = wall_clock64(); } while (0)
-#else
-#define CKV_STAMP(i) do { } while (0)
-#endif
 
 template <int DT, int DH, int NQ, int WT, int QPH>
 __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArgs a, FusedArgs f) {
@@ -254,11 +250,8 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArg
     const char *kwave = kbase + (int64_t)t_begin * a.ks_t;
     const int next_unit = unit + n_active;
     float2 *const part = f.fpart + (size_t)(k & 1) * NPH * grid * RP;
-
-    CKV_STAMP(0);
     wait_vm<0>();
     __syncthreads();  // Q of this unit is in the Q area, the first key tiles are in the ring
-    CKV_STAMP(1);
 
     chunk_t qf[QPH][NCH];
     chunk_t kres[kFusedRes][NCH];
@@ -331,7 +324,6 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArg
         }
         if (ph == 0) wait_vm<0>();
       }
-      if (ph == 0) CKV_STAMP(2);
       for (int t = n_fast; t < ntw; ++t) {  // tiles outside the pipeline, masked
         const int t0 = t_begin + t * kTile;
         chunk_t kreg[NCH];
@@ -366,8 +358,6 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArg
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-
-    CKV_STAMP(3);
     // ======================= pass 2: column sums, phase by phase ==============================
 #pragma unroll
     for (int ph = 0; ph < NPH; ++ph) {
@@ -377,7 +367,6 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArg
       if (tid == 0)
         spin_until(&f.sync[16 + kFusedMaxPhases * xcc + ph], (uint32_t)(k + 1) * (uint32_t)nx, status);
       __syncthreads();
-      if (ph == 0) CKV_STAMP(4);
       {
         const int grp = tid / RP, row = tid % RP;
         const int per = (nx + NSPLIT - 1) / NSPLIT;
@@ -425,7 +414,6 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArg
         s_bias[wave][lane] = bs.q;
       }
       __syncthreads();
-      if (ph == 0) CKV_STAMP(5);
       // From here on nobody reads this unit's Q area again (the last phase has its tiles in registers).
       if (ph == NPH - 1 && next_unit < f.units) prefetch_q(next_unit);
 
@@ -481,13 +469,11 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) fused_scan_kernel(ScoreArg
         }
         store_column_sums<QPH>(a, bc, cs, WT, kt, hh);
       }
-      if (ph == 0) CKV_STAMP(6);
     }
     if (!early_k && next_unit < f.units) {
       wait_vm<0>();
       prefetch_k(next_unit);
     }
-    CKV_STAMP(7);
   }
 }
 

@@ -7,7 +7,7 @@ namespace ckv {
 
 hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Workspace &w, const void *q,
                                 const void *k, const float *lse_in, float *lse_out, float *scores,
-                                char *ws, hipStream_t stream) {
+                                char *ws, hipStream_t stream, const UtilityFusion *fuse) {
   ScoreArgs a;
   a.q = (const char *)q;
   a.k = (const char *)k;
@@ -26,6 +26,11 @@ hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Works
   a.lse_out = lse_out ? lse_out : (float *)(ws + w.lse_off);
   a.lse = lse_in ? lse_in : a.lse_out;
   a.scores = scores;
+  a.w_row = fuse ? fuse->w_row : nullptr;
+  a.utility = fuse ? fuse->utility : nullptr;
+  a.pool = fuse ? fuse->pool : CKV_POOL_NONE;
+  a.radius = fuse ? fuse->radius : 0;
+  a.inv_kernel = fuse ? fuse->inv_kernel : 1.0f;
   const bool need_lse = lse_in == nullptr, need_scores = scores != nullptr;
   FusedLaunch fl;
   const FusedLaunch *use_fused = nullptr;

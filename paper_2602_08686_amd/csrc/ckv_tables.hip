@@ -13,6 +13,7 @@ constexpr int kTablesThreads = 256;
 constexpr int kTablesPerThread = 4;
 constexpr int kTablesTile = kTablesThreads * kTablesPerThread;  // 1024 positions
 constexpr int kMaxHalo = 31;                                    // pool_kernel <= 63
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 struct TablesArgs {
   const float *scores;  // [Bz][Hq][T]
@@ -77,22 +78,24 @@ __device__ void write_budgets(const TablesArgs &a, int b) {
   }
 }
 
+__device__ __forceinline__ void write_tau_and_budgets(const TablesArgs &a, int b) {
+  float tau = 0.0f;
+  if (a.gate_layer) {
+    const int be = min(max(a.risk_bins[2 * b], 0), a.n_ent - 1);
+    const int bp = min(max(a.risk_bins[2 * b + 1], 0), a.n_ppl - 1);
+    tau = a.gate_layer[be * a.n_ppl + bp];
+  }
+  a.tau[b] = tau;
+  write_budgets(a, b);
+}
+
 __global__ void __launch_bounds__(kTablesThreads) tables_kernel(TablesArgs a) {
   __shared__ float sm[kTablesTile + 2 * kMaxHalo];
   const int unit = blockIdx.y, tile = blockIdx.x;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
   const int t0 = tile * kTablesTile;
 
-  if (tile == 0 && g == 0 && threadIdx.x == 0) {
-    float tau = 0.0f;
-    if (a.gate_layer) {
-      const int be = min(max(a.risk_bins[2 * b], 0), a.n_ent - 1);
-      const int bp = min(max(a.risk_bins[2 * b + 1], 0), a.n_ppl - 1);
-      tau = a.gate_layer[be * a.n_ppl + bp];
-    }
-    a.tau[b] = tau;
-    write_budgets(a, b);
-  }
+  if (tile == 0 && g == 0 && threadIdx.x == 0) write_tau_and_budgets(a, b);
   if (a.P == 0) return;
 
   float best[kTablesPerThread];
@@ -143,24 +146,10 @@ __global__ void __launch_bounds__(kTablesThreads) tables_kernel(TablesArgs a) {
 // four consecutive positions and reads them plus the four on either side as three 128-bit loads per
 // head (the neighbours' loads hit L1), pools from registers with the taps unrolled, and writes one
 // 128-bit store (or scalars where P is not a multiple of four). No LDS and no barriers.
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-
+// Utilities of the four positions t .. t + 3 (t a multiple of four, t < P) of one (batch, KV head).
 template <int POOL, int R>
-__global__ void __launch_bounds__(kTablesThreads) tables_window_kernel(TablesArgs a) {
-  const int unit = blockIdx.y;
+__device__ __forceinline__ void pool_four(const TablesArgs &a, int unit, int t) {
   const int b = unit / a.Hkv, g = unit % a.Hkv;
-  const int t = (blockIdx.x * kTablesThreads + threadIdx.x) * 4;  // first of this thread's positions
-  if (blockIdx.x == 0 && g == 0 && threadIdx.x == 0) {
-    float tau = 0.0f;
-    if (a.gate_layer) {
-      const int be = min(max(a.risk_bins[2 * b], 0), a.n_ent - 1);
-      const int bp = min(max(a.risk_bins[2 * b + 1], 0), a.n_ppl - 1);
-      tau = a.gate_layer[be * a.n_ppl + bp];
-    }
-    a.tau[b] = tau;
-    write_budgets(a, b);
-  }
-  if (t >= a.P) return;
   const float pad = POOL == CKV_POOL_MAX ? -INFINITY : 0.0f;
   float rho[4] = {1.0f, 1.0f, 1.0f, 1.0f};
   if (a.rho) {
@@ -205,6 +194,45 @@ __global__ void __launch_bounds__(kTablesThreads) tables_window_kernel(TablesArg
   }
 }
 
+template <int POOL, int R>
+__global__ void __launch_bounds__(kTablesThreads) tables_window_kernel(TablesArgs a) {
+  const int unit = blockIdx.y;
+  const int t = (blockIdx.x * kTablesThreads + threadIdx.x) * 4;  // first of this thread's positions
+  if (blockIdx.x == 0 && unit % a.Hkv == 0 && threadIdx.x == 0) write_tau_and_budgets(a, unit / a.Hkv);
+  if (t >= a.P) return;
+  pool_four<POOL, R>(a, unit, t);
+}
+
+// Companion of the fused utility form of the scan's second pass. That pass writes the utilities of
+// the keys its pipeline takes (whole 128-key rounds at the front of every wave's key range) except
+// the first four and the last four of them, and stores raw column sums only around those two places
+// and for the tail of the range. This kernel computes what is missing from the raw sums: per wave
+// range the four-key group at the front, the last group of the pipelined part, and every group of the
+// tail. One workgroup of 64 threads per (wave range, unit); also writes tau and the budgets.
+struct FixupArgs {
+  int keys_per_wave, n_ranges;  // the scan's split of the key axis
+};
+constexpr int kFixupThreads = 64;
+constexpr int kScanBlockKeys = 128;  // keys per pipeline round of the scan (4 tiles of 32)
+
+template <int POOL, int R>
+__global__ void __launch_bounds__(kFixupThreads) tables_fixup_kernel(TablesArgs a, FixupArgs f) {
+  const int unit = blockIdx.y, range = blockIdx.x;
+  if (range == 0 && unit % a.Hkv == 0 && threadIdx.x == 0) write_tau_and_budgets(a, unit / a.Hkv);
+  const int t_begin = range * f.keys_per_wave;
+  if (t_begin >= a.T) return;
+  const int t_end = min(t_begin + f.keys_per_wave, a.T);
+  const int n_full = max(0, (min(t_end, a.P) - t_begin) / 32);   // tiles wholly inside the prefix
+  const int n_blocks = n_full / 4;                               // pipeline rounds
+  const int tail0 = t_begin + n_blocks * kScanBlockKeys, tail1 = min(t_end, a.P);
+  const int n_tail = tail1 > tail0 ? (tail1 - tail0 + 3) / 4 : 0;
+  const int n_edge = n_blocks > 0 ? 2 : 0;
+  for (int i = threadIdx.x; i < n_edge + n_tail; i += kFixupThreads) {
+    const int t = i < n_edge ? (i == 0 ? t_begin : tail0 - 4) : tail0 + (i - n_edge) * 4;
+    pool_four<POOL, R>(a, unit, t);
+  }
+}
+
 template <int POOL>
 static bool launch_window_pool(const TablesArgs &a, dim3 grid, hipStream_t stream) {
   const dim3 block(kTablesThreads);
@@ -218,10 +246,10 @@ static bool launch_window_pool(const TablesArgs &a, dim3 grid, hipStream_t strea
   return false;
 }
 
-hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,
-                               const float *vnorm_ratio, const float *w_head, const float *head_share,
-                               const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
-                               float *utility, int32_t *budget, float *tau, hipStream_t stream) {
+static TablesArgs tables_args(const ckv_params *p, const Shape &s, const float *scores,
+                              const float *vnorm_ratio, const float *w_head, const float *head_share,
+                              const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
+                              float *utility, int32_t *budget, float *tau) {
   TablesArgs a;
   a.scores = scores;
   a.rho = (p->flags & CKV_FLAG_VALUE_NORM) ? vnorm_ratio : nullptr;
@@ -240,6 +268,15 @@ hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float 
   a.radius = a.kernel / 2;
   a.B = p->budget_per_kv_head;
   a.n_tiles = s.P > 0 ? (s.P + kTablesTile - 1) / kTablesTile : 1;
+  return a;
+}
+
+hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,
+                               const float *vnorm_ratio, const float *w_head, const float *head_share,
+                               const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
+                               float *utility, int32_t *budget, float *tau, hipStream_t stream) {
+  const TablesArgs a = tables_args(p, s, scores, vnorm_ratio, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,
+                                   utility, budget, tau);
   const dim3 grid(a.n_tiles, s.Bz * s.Hkv), block(kTablesThreads);
   const bool aligned = s.T % 4 == 0 && ((uintptr_t)scores % 16 == 0) && ((uintptr_t)utility % 16 == 0) &&
                        (!a.rho || (uintptr_t)a.rho % 16 == 0);
@@ -248,6 +285,34 @@ hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float 
     done = p->pool == CKV_POOL_MAX ? launch_window_pool<CKV_POOL_MAX>(a, grid, stream)
                                    : launch_window_pool<CKV_POOL_AVG>(a, grid, stream);
   if (!done) hipLaunchKernelGGL(tables_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+template <int POOL>
+static void launch_fixup_pool(const TablesArgs &a, const FixupArgs &f, dim3 grid, hipStream_t stream) {
+  const dim3 block(kFixupThreads);
+  switch (a.radius) {
+    case 0: hipLaunchKernelGGL((tables_fixup_kernel<POOL, 0>), grid, block, 0, stream, a, f); break;
+    case 1: hipLaunchKernelGGL((tables_fixup_kernel<POOL, 1>), grid, block, 0, stream, a, f); break;
+    case 2: hipLaunchKernelGGL((tables_fixup_kernel<POOL, 2>), grid, block, 0, stream, a, f); break;
+    default: hipLaunchKernelGGL((tables_fixup_kernel<POOL, 3>), grid, block, 0, stream, a, f); break;
+  }
+}
+
+// The caller has checked utility_fast_path(): no value norm, radius <= 3, T and P multiples of four,
+// 16-byte aligned scores and utility.
+hipError_t launch_utility_fixup(const ckv_params *p, const Shape &s, const float *sparse_scores,
+                                const float *w_head, const float *head_share, const float *t_gate, int n_ent,
+                                int n_ppl, const int32_t *risk_bins, float *utility, int32_t *budget, float *tau,
+                                hipStream_t stream) {
+  const TablesArgs a = tables_args(p, s, sparse_scores, nullptr, w_head, head_share, t_gate, n_ent, n_ppl,
+                                   risk_bins, utility, budget, tau);
+  FixupArgs f;
+  f.keys_per_wave = s.keys_per_wave;
+  f.n_ranges = s.n_chunks * kScoreWaves;
+  const dim3 grid(f.n_ranges, s.Bz * s.Hkv);
+  if (p->pool == CKV_POOL_MAX) launch_fixup_pool<CKV_POOL_MAX>(a, f, grid, stream);
+  else launch_fixup_pool<CKV_POOL_AVG>(a, f, grid, stream);
   return hipGetLastError();
 }
 
