@@ -744,22 +744,25 @@ __device__ __forceinline__ void flush_column_sums(const ScoreArgs &a, const Bloc
 
 // Fused form of the flush (ckv_window_utility): instead of the column sums, the wave writes the
 // UTILITY -- pooled along the keys, weighted per head, maximum over the group's heads (paper Eq. 6) --
-// straight from the stage. A stage row holds, in front of the block's 128 values, the last eight of
-// the previous block, and each flush covers the 128 keys that END four keys before the block does,
-// so every pooling window (radius <= 3) lies inside the row. What this leaves out per wave range --
-// the first four keys, the last four keys of the pipelined part, and the tail tiles -- a small kernel
-// computes afterwards from raw column sums, which the first block (its first eight keys), the last
-// block (its last eight keys) and the tail tiles store. Lanes 0..31 take the even heads of the group,
-// lanes 32..63 the odd ones, four consecutive keys each (three 128-bit reads per head); the halves
-// then swap so that each lane ends up with the group maximum of two adjacent keys and stores them
-// with one 64-bit store. The taps are combined left to right, as the stand-alone tables kernel does.
-constexpr int kUtilCarry = 8;     // values of the previous block kept in front of a stage row
+// straight from the stage. A stage row holds, in front of the block's 128 values, the last 40 of the
+// previous block, and each flush covers the 128 keys that END 32 keys before the block does: every
+// pooling window (radius <= 3) lies inside the row and every store covers whole 128-byte lines
+// (partial lines proved expensive). What this leaves out per wave range -- the first four keys, the
+// last 32 keys of the pipelined part, and the tail tiles -- a small kernel computes afterwards from
+// raw column sums, which the first block (its first eight keys), the last block (its last 40 keys)
+// and the tail tiles store. Lanes 0..31 take the even heads of the group, lanes 32..63 the odd ones,
+// four consecutive keys each (three 128-bit reads per head); the halves then swap so that each lane
+// ends up with the group maximum of two adjacent keys and stores them with one 64-bit store. The taps
+// are combined left to right, as the stand-alone tables kernel does.
+constexpr int kUtilShift = 32;    // a flush covers the 128 keys that end this many keys before the block does
+constexpr int kUtilCarry = 40;    // values of the previous block kept in front of a stage row (shift + 8)
+constexpr int kUtilHead = 8;      // raw column sums stored at the front of a range's first block
 constexpr int kUtilRow = kUtilCarry + kRing * kTile;
 constexpr int kUtilMaxRadius = 3; // pooling kernels of up to 7 taps
 template <int NH, int POOL, int R>
 __device__ __forceinline__ void pooled_group_max(const ScoreArgs &a, const float *rows, int lane, int heads_left,
                                                  const float (&wgt)[NH], float (&best)[4]) {
-  const int half = lane >> 5, grp = lane & 31;  // keys 4 grp - 4 .. 4 grp - 1 of the block
+  const int half = lane >> 5, grp = lane & 31;  // keys 4 grp - 32 .. 4 grp - 29 of the block
 #pragma unroll
   for (int e = 0; e < 4; ++e) best[e] = -INFINITY;
 #pragma unroll
@@ -767,7 +770,7 @@ __device__ __forceinline__ void pooled_group_max(const ScoreArgs &a, const float
     const int h = 2 * hp + half;
     if (2 * hp >= heads_left) break;
     const bool live = h < NH && h < heads_left;
-    const float *row = rows + (live ? h : 0) * kUtilRow + 4 * grp;  // row[4 .. 7] are this lane's keys
+    const float *row = rows + (live ? h : 0) * kUtilRow + (kUtilCarry - kUtilShift - 4) + 4 * grp;  // row[4 .. 7]: this lane's keys
     float w[12];
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
@@ -807,7 +810,7 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
   for (int h = 0; h < NH; h += 2) {
     const int mine = h + (lane >> 5), key4 = 4 * (lane & 31);
     const bool valid = mine < NH && mine < heads_left &&
-                       ((first_block && key4 < kUtilCarry) || (last_block && key4 >= BLK - kUtilCarry));
+                       ((first_block && key4 < kUtilHead) || (last_block && key4 >= BLK - kUtilCarry));
     const f32x4 v = *reinterpret_cast<const f32x4 *>(rows + (mine < NH ? mine : 0) * kUtilRow + kUtilCarry + key4);
     const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + t_first + key4) * 4) : 0x80000000u;
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, 0);
@@ -835,17 +838,19 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
   const f32x2 out = {fmaxf(__uint_as_float(s02[0]), __uint_as_float(s02[1])),
                      fmaxf(__uint_as_float(s13[0]), __uint_as_float(s13[1]))};
   const int grp = lane & 31;
-  // group 0 lies in front of the block; in the range's first block it and group 1 (the range's first
-  // four keys, whose windows reach in front of the range) are left to the fix-up kernel
-  const bool emit = grp >= 2 || !first_block;
+  // groups 0..7 lie in front of the block; in the range's first block they and group 8 (the range's
+  // first four keys, whose windows reach in front of the range) are left to the fix-up kernel
+  const bool emit = grp >= kUtilShift / 4 + 1 || !first_block;
   const uint32_t off_u =
-      emit ? (uint32_t)((bc.g * a.P + t_first - 4 + 4 * grp + 2 * (lane >> 5)) * 4) : 0x80000000u;
+      emit ? (uint32_t)((bc.g * a.P + t_first - kUtilShift + 4 * grp + 2 * (lane >> 5)) * 4) : 0x80000000u;
   __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, out), rsrc_u, off_u, 0, 0);
-  // carry: the block's last eight values move in front of the rows for the next block
-  if (lane < 2 * NH) {
-    float *row = rows + (lane >> 1) * kUtilRow;
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(row + kUtilCarry + BLK - kUtilCarry + 4 * (lane & 1));
-    *reinterpret_cast<f32x4 *>(row + 4 * (lane & 1)) = v;
+  // carry: the block's last kUtilCarry values move in front of the rows for the next block
+  constexpr int PER = kUtilCarry / 4;  // 128-bit pieces per head
+  static_assert(PER * NH <= kWave, "one piece per lane");
+  if (lane < PER * NH) {
+    float *row = rows + (lane / PER) * kUtilRow;
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(row + BLK + 4 * (lane % PER));
+    *reinterpret_cast<f32x4 *>(row + 4 * (lane % PER)) = v;
   }
 }
 

@@ -205,15 +205,18 @@ __global__ void __launch_bounds__(kTablesThreads) tables_window_kernel(TablesArg
 
 // Companion of the fused utility form of the scan's second pass. That pass writes the utilities of
 // the keys its pipeline takes (whole 128-key rounds at the front of every wave's key range) except
-// the first four and the last four of them, and stores raw column sums only around those two places
-// and for the tail of the range. This kernel computes what is missing from the raw sums: per wave
-// range the four-key group at the front, the last group of the pipelined part, and every group of the
-// tail. One workgroup of 64 threads per (wave range, unit); also writes tau and the budgets.
+// the first four and the last kScanTrail of them (its output windows trail the rounds by that much so
+// that its stores stay 128-byte aligned), and stores raw column sums only around those two places and
+// for the tail of the range. This kernel computes what is missing from the raw sums: per wave range
+// the four-key group at the front, the last kScanTrail / 4 groups of the pipelined part, and every
+// group of the tail. One workgroup of 64 threads per (wave range, unit); also writes tau and the
+// budgets.
 struct FixupArgs {
   int keys_per_wave, n_ranges;  // the scan's split of the key axis
 };
 constexpr int kFixupThreads = 64;
 constexpr int kScanBlockKeys = 128;  // keys per pipeline round of the scan (4 tiles of 32)
+constexpr int kScanTrail = 32;       // pipelined keys at the end of a range that the scan leaves to this kernel
 
 template <int POOL, int R>
 __global__ void __launch_bounds__(kFixupThreads) tables_fixup_kernel(TablesArgs a, FixupArgs f) {
@@ -226,9 +229,9 @@ __global__ void __launch_bounds__(kFixupThreads) tables_fixup_kernel(TablesArgs 
   const int n_blocks = n_full / 4;                               // pipeline rounds
   const int tail0 = t_begin + n_blocks * kScanBlockKeys, tail1 = min(t_end, a.P);
   const int n_tail = tail1 > tail0 ? (tail1 - tail0 + 3) / 4 : 0;
-  const int n_edge = n_blocks > 0 ? 2 : 0;
+  const int n_edge = n_blocks > 0 ? 1 + kScanTrail / 4 : 0;
   for (int i = threadIdx.x; i < n_edge + n_tail; i += kFixupThreads) {
-    const int t = i < n_edge ? (i == 0 ? t_begin : tail0 - 4) : tail0 + (i - n_edge) * 4;
+    const int t = i < n_edge ? (i == 0 ? t_begin : tail0 - kScanTrail + (i - 1) * 4) : tail0 + (i - n_edge) * 4;
     pool_four<POOL, R>(a, unit, t);
   }
 }
