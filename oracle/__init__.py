@@ -209,3 +209,76 @@ def retention_layer(q, k, v_bits, v=None, *, W, mode, kernel, B, cap, w_head_row
     if v_bits is not None:
         out["v_out"] = gather(v_bits, idx, count)
     return out
+
+
+# ---------------------------------------------------------------------------------------------------
+# Layer-shared mode: Alg. 1 as printed -- one window mass alpha per prompt (the mean over all layers and
+# heads, steps (A)), the structural risk coordinate, and per layer one utility vector and one index set
+# shared by all heads (stages (B)-(D)). Plain numpy in float64, one statement per step of the listing.
+# ---------------------------------------------------------------------------------------------------
+def alpha_mean(scores_per_layer):
+    """Per-head window masses of every layer, each [Bz,Hq,T] (already scaled by T/W) -> alpha [Bz,T]:
+    alpha = (T/|Omega|) sum_j Abar[j,:] with Abar the mean of A over layers and heads (Eq. 4)."""
+    stack = np.stack([np.asarray(s, dtype=np.float64) for s in scores_per_layer])   # [L,Bz,Hq,T]
+    return stack.mean(axis=(0, 2))
+
+
+def risk_struct(alpha):
+    """alpha [Bz,T] -> structural risk [Bz]: entropy (natural log) of A' = alpha / ||alpha||_1 (Alg. 1 (A),
+    Eq. 7); terms with A'_t = 0 contribute 0."""
+    a = np.asarray(alpha, dtype=np.float64)
+    p = a / a.sum(axis=-1, keepdims=True)
+    terms = np.where(p > 0, p * np.log(np.where(p > 0, p, 1.0)), 0.0)
+    return -terms.sum(axis=-1)
+
+
+def discretize(value, edges):
+    """Bin index of each value for ascending bin edges e_0 < e_1 < ...: the number of edges <= value
+    (so n edges make n + 1 bins; the paper leaves the edges to the table's compiler)."""
+    v = np.atleast_1d(np.asarray(value, dtype=np.float64))
+    e = np.asarray(edges, dtype=np.float64)
+    return np.array([int((e <= x).sum()) for x in v], dtype=np.int32)
+
+
+def shared_utility(alpha, rho, w_head_row, W):
+    """alpha [Bz,T], rho [Bz,Hkv,T], w_head_row [Hq] -> u_hat [Bz,P] float32 (Alg. 1 stages (B)-(C)):
+    u^(h) = alpha * rho^(kv head of h); u_hat = max over ALL query heads of fp32(W_head[h] * u^(h))."""
+    a = np.asarray(alpha, dtype=np.float64)
+    r = np.asarray(rho, dtype=np.float64)
+    w = np.asarray(w_head_row, dtype=np.float32)
+    Bz, T = a.shape
+    Hkv, Hq = r.shape[1], w.shape[0]
+    G = Hq // Hkv
+    P = T - int(W)
+    best = np.full((Bz, P), -np.inf, dtype=np.float32)
+    for h in range(Hq):
+        u_h = a[:, :P] * r[:, h // G, :P]
+        best = np.maximum(best, (np.float64(w[h]) * u_h).astype(np.float32))
+    return best
+
+
+def gather_shared(src, idx, count):
+    """src [Bz,Hkv,T,...], idx [Bz,cap], count [Bz] -> [Bz,Hkv,cap,...]: every head of a layer keeps the
+    same positions (Alg. 1: S^(l) is shared across heads within layer l)."""
+    src = np.ascontiguousarray(src)
+    Bz, Hkv = src.shape[:2]
+    return gather(src, np.repeat(np.asarray(idx, np.int32)[:, None, :], Hkv, axis=1),
+                  np.repeat(np.asarray(count, np.int32)[:, None], Hkv, axis=1))
+
+
+def layer_shared_layer(alpha, k_bits, v_bits, v, *, W, B_layer, cap, w_head_row, gate_layer=None, risk_bins=None):
+    """Stages (B)-(D) of Alg. 1 for one layer given the prompt's alpha: rho, u_hat, tau, the shared index
+    set (window forced in, as in the per-head mode) and the gathered K/V."""
+    a = np.asarray(alpha, dtype=np.float64)
+    Bz = a.shape[0]
+    rho = value_norm_ratio(v)
+    u = shared_utility(a, rho, w_head_row, W)
+    if gate_layer is None:
+        tau_b = np.zeros((Bz,), dtype=np.float32)
+    else:
+        tau_b = np.array([tau(gate_layer, risk_bins[b][0], risk_bins[b][1]) for b in range(Bz)], dtype=np.float32)
+    bud = np.full((Bz, 1), int(B_layer), dtype=np.int32)
+    idx, count = select(u[:, None, :], tau_b, bud, W, cap)
+    idx, count = idx[:, 0], count[:, 0]
+    return dict(rho=rho, utility=u, tau=tau_b, idx=idx, count=count,
+                k_out=gather_shared(k_bits, idx, count), v_out=gather_shared(v_bits, idx, count))

@@ -102,6 +102,34 @@ def test_null_pointers_and_workspace_errors():
     assert lib.ckv_window_scores(None, dummy, dummy, None, None, dummy, None, dummy, need, None) == B.CKV_EINVAL
 
 
+def test_window_utility_and_scan_flags_are_validated_on_the_host():
+    lib = B.load()
+    p = _good()
+    d = ctypes.c_void_p(256)
+    need = B.ckv_workspace_bytes(p)
+    wu = lambda prm, **kw: lib.ckv_window_utility(
+        ctypes.byref(prm), kw.get("q", d), d, kw.get("v"), None, kw.get("w_head", d), None, kw.get("t_gate"),
+        kw.get("n_ent", 0), 0, None, kw.get("scratch", d), kw.get("rho"), d, d, d, kw.get("ws", d),
+        kw.get("ws_bytes", need), None)
+    assert wu(p, q=None) == B.CKV_EINVAL
+    assert wu(p, w_head=None) == B.CKV_EINVAL
+    assert wu(p, scratch=None) == B.CKV_EINVAL
+    assert wu(p, t_gate=d, n_ent=20) == B.CKV_EINVAL            # gate without risk bins
+    assert wu(p, ws=None) == B.CKV_EWORKSPACE
+    assert wu(p, ws_bytes=need - 1) == B.CKV_EWORKSPACE
+    assert wu(_good(flags=B.FLAG_VALUE_NORM)) == B.CKV_EINVAL   # value norm without v / rho
+    assert wu(_good(pool_kernel=6)) == B.CKV_EINVAL
+    # the two scan flags exclude each other; either alone is accepted; the status word exists for bf16
+    both = _good(flags=B.FLAG_SCAN_TWO_KERNELS | B.FLAG_SCAN_SINGLE_READ)
+    assert B.ckv_workspace_bytes(both) == 0
+    for f in (B.FLAG_SCAN_TWO_KERNELS, B.FLAG_SCAN_SINGLE_READ):
+        assert B.ckv_workspace_bytes(_good(flags=f)) == need
+    off = B.ckv_scan_status_offset(p)
+    assert 0 <= off < need and off % 4 == 0
+    assert B.ckv_scan_status_offset(_good(dtype=torch.float32, head_dim=64)) == -1
+    assert B.ckv_scan_status_offset(both) == -1
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         B.load(tmp_path / "libckv.so")
