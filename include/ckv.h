@@ -221,6 +221,59 @@ ckv_status ckv_compact_kv(const ckv_params *params, const void *k, const void *v
                           const int32_t *count, void *k_out, void *v_out, void *hip_stream);
 
 /* Static text for a status code; never NULL. */
+/*
+ * Layer-shared mode: the paper's Alg. 1 as printed, where ONE window mass alpha serves every layer and
+ * head and every layer keeps ONE index set for all its heads. Order of calls for a prompt:
+ *   for each layer: ckv_window_scores (with CKV_FLAG_VALUE_NORM: rho of that layer) and
+ *                   ckv_alpha_accumulate(weight = 1 / (n_layers * Hq))                  -- Alg. 1 (A)
+ *   once:           ckv_risk_struct                                                     -- Alg. 1 (A)
+ *   for each layer: ckv_shared_utility, ckv_select_topk with a one-head ckv_params (batch, 1 query head,
+ *                   1 KV head, budget = B_l; utility [Bz,1,P], budget [Bz,1]), ckv_compact_kv_shared.
+ *
+ * ckv_alpha_accumulate: alpha[b,t] += weight * sum_h scores[b,h,t]. With weight = 1/(L*Hq) over all
+ * layers this is alpha = (T/W) sum_{j in Omega} Abar[j,:] for Abar the mean of A over layers and heads
+ * (paper Eq. 4, Alg. 1 (A)); sum_t alpha = T.
+ *   scores  in      [Bz,Hq,T] fp32 of one layer (from ckv_window_scores)
+ *   alpha   in/out  [Bz,T] fp32; the caller clears it before the first layer
+ */
+ckv_status ckv_alpha_accumulate(const ckv_params *params, const float *scores, float weight, float *alpha,
+                                void *hip_stream);
+
+/*
+ * Structural risk coordinate (paper Eq. 7, Alg. 1 (A)): risk[b] = -sum_t A'_t ln A'_t with
+ * A' = alpha[b,:] / ||alpha[b,:]||_1 (terms with A'_t = 0 count as 0), and its bin
+ * bin[b] = number of ent_edges <= risk[b] (ascending edges chosen by whoever compiled T_gate; the
+ * paper does not fix them). Sums are formed in fp64 in a fixed order.
+ *   alpha      in   [Bz,T] fp32, non-negative
+ *   ent_edges  in   [n_edges] fp32 ascending (device), may be NULL when bin is NULL or n_edges = 0
+ *   risk       out  [Bz] fp32           bin  out  [Bz] int32, or NULL
+ */
+ckv_status ckv_risk_struct(const ckv_params *params, const float *alpha, const float *ent_edges,
+                           int32_t n_edges, float *risk, int32_t *bin, void *hip_stream);
+
+/*
+ * One utility vector per layer (paper Eq. 4 u = alpha * rho, Eq. 6, Alg. 1 (B)-(C)) and the gate
+ * lookup (Sec. 4.3): for t in [0, P)
+ *     utility[b,t] = max over ALL query heads h of fp32(w_head[layer,h] * (alpha[b,t] * vnorm_ratio[b,g(h),t]))
+ *     tau[b]       = t_gate[layer, risk_bins[b,0], risk_bins[b,1]]      (0 if t_gate is NULL)
+ * (the pooling fields of params are not used: the paper has no pooling).
+ *   alpha        in   [Bz,T] fp32          vnorm_ratio  in  [Bz,Hkv,T] fp32 of this layer
+ *   w_head, t_gate, n_ent, n_ppl, risk_bins   as for ckv_apply_tables
+ *   utility      out  [Bz,P] fp32          tau  out  [Bz] fp32
+ */
+ckv_status ckv_shared_utility(const ckv_params *params, const float *alpha, const float *vnorm_ratio,
+                              const float *w_head, const float *t_gate, int32_t n_ent, int32_t n_ppl,
+                              const int32_t *risk_bins, float *utility, float *tau, void *hip_stream);
+
+/*
+ * Gather with one index set per batch element, shared by all KV heads of the layer (paper Alg. 1
+ * Gather_tok: "S^(l) is shared across heads within layer l"): for r < count[b], every g
+ *     k_out[b,g,r,:] = k[b,g,idx[b,r],:]    v_out[b,g,r,:] = v[b,g,idx[b,r],:]     (bit copies)
+ *   idx  in  [Bz,cap] int32      count  in  [Bz] int32      k_out, v_out  out  [Bz,Hkv,cap,d]
+ */
+ckv_status ckv_compact_kv_shared(const ckv_params *params, const void *k, const void *v, const int32_t *idx,
+                                 const int32_t *count, void *k_out, void *v_out, void *hip_stream);
+
 const char *ckv_status_string(ckv_status status);
 
 #ifdef __cplusplus

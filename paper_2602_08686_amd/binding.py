@@ -22,7 +22,8 @@ FLAG_SCAN_TWO_KERNELS = 2   # force the scan that streams K twice
 FLAG_SCAN_SINGLE_READ = 4   # force the persistent scan that reads K once (where it exists)
 
 EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
-           "ckv_compact_kv", "ckv_status_string")
+           "ckv_compact_kv", "ckv_alpha_accumulate", "ckv_risk_struct", "ckv_shared_utility", "ckv_compact_kv_shared",
+           "ckv_status_string")
 
 
 class CkvParams(ctypes.Structure):
@@ -72,6 +73,14 @@ def load(path: Optional[Path] = None):
     lib.ckv_select_topk.restype = ctypes.c_int
     lib.ckv_compact_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
     lib.ckv_compact_kv.restype = ctypes.c_int
+    lib.ckv_alpha_accumulate.argtypes = [pp, vp, ctypes.c_float, vp, vp]
+    lib.ckv_alpha_accumulate.restype = ctypes.c_int
+    lib.ckv_risk_struct.argtypes = [pp, vp, vp, ctypes.c_int32, vp, vp, vp]
+    lib.ckv_risk_struct.restype = ctypes.c_int
+    lib.ckv_shared_utility.argtypes = [pp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
+    lib.ckv_shared_utility.restype = ctypes.c_int
+    lib.ckv_compact_kv_shared.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ckv_compact_kv_shared.restype = ctypes.c_int
     lib.ckv_status_string.argtypes = [ctypes.c_int]
     lib.ckv_status_string.restype = ctypes.c_char_p
     if path is None:
@@ -181,6 +190,29 @@ def ckv_select_topk(params, utility, budget, tau, idx, count, workspace=None, st
 def ckv_compact_kv(params, k, v, idx, count, k_out, v_out, stream=None):
     _check(load().ckv_compact_kv(ctypes.byref(params), _ptr(k), _ptr(v), _ptr(idx), _ptr(count),
                                  _ptr(k_out), _ptr(v_out), _stream(stream)), "ckv_compact_kv")
+
+
+def ckv_alpha_accumulate(params, scores, weight, alpha, stream=None):
+    _check(load().ckv_alpha_accumulate(ctypes.byref(params), _ptr(scores), float(weight), _ptr(alpha),
+                                       _stream(stream)), "ckv_alpha_accumulate")
+
+
+def ckv_risk_struct(params, alpha, ent_edges, risk, bins=None, stream=None):
+    n = 0 if ent_edges is None else ent_edges.numel()
+    _check(load().ckv_risk_struct(ctypes.byref(params), _ptr(alpha), _ptr(ent_edges), int(n), _ptr(risk),
+                                  _ptr(bins), _stream(stream)), "ckv_risk_struct")
+
+
+def ckv_shared_utility(params, alpha, vnorm_ratio, w_head, t_gate, n_ent, n_ppl, risk_bins, utility, tau,
+                       stream=None):
+    _check(load().ckv_shared_utility(ctypes.byref(params), _ptr(alpha), _ptr(vnorm_ratio), _ptr(w_head),
+                                     _ptr(t_gate), int(n_ent), int(n_ppl), _ptr(risk_bins), _ptr(utility),
+                                     _ptr(tau), _stream(stream)), "ckv_shared_utility")
+
+
+def ckv_compact_kv_shared(params, k, v, idx, count, k_out, v_out, stream=None):
+    _check(load().ckv_compact_kv_shared(ctypes.byref(params), _ptr(k), _ptr(v), _ptr(idx), _ptr(count),
+                                        _ptr(k_out), _ptr(v_out), _stream(stream)), "ckv_compact_kv_shared")
 
 
 class LayerBuffers:

@@ -286,6 +286,57 @@ extern "C" ckv_status ckv_compact_kv(const ckv_params *params, const void *k, co
   return CKV_OK;
 }
 
+extern "C" ckv_status ckv_alpha_accumulate(const ckv_params *params, const float *scores, float weight,
+                                           float *alpha, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!scores || !alpha || !isfinite(weight)) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_alpha_accumulate(s, scores, weight, alpha, (hipStream_t)hip_stream) != hipSuccess) return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_risk_struct(const ckv_params *params, const float *alpha, const float *ent_edges,
+                                      int32_t n_edges, float *risk, int32_t *bin, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!alpha || !risk || n_edges < 0 || (bin && n_edges > 0 && !ent_edges)) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_risk_struct(s, alpha, ent_edges, n_edges, risk, bin, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_shared_utility(const ckv_params *params, const float *alpha, const float *vnorm_ratio,
+                                         const float *w_head, const float *t_gate, int32_t n_ent, int32_t n_ppl,
+                                         const int32_t *risk_bins, float *utility, float *tau, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!alpha || !vnorm_ratio || !w_head || !utility || !tau) return CKV_EINVAL;
+  if (t_gate && (n_ent < 1 || n_ppl < 1 || !risk_bins)) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_shared_utility(params, s, alpha, vnorm_ratio, w_head, t_gate, n_ent, n_ppl, risk_bins, utility, tau,
+                            (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_compact_kv_shared(const ckv_params *params, const void *k, const void *v,
+                                            const int32_t *idx, const int32_t *count, void *k_out, void *v_out,
+                                            void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!k || !v || !idx || !count || !k_out || !v_out) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_gather(params, s, k, v, idx, count, k_out, v_out, (hipStream_t)hip_stream, true) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
 extern "C" const char *ckv_status_string(ckv_status status) {
   switch (status) {
     case CKV_OK: return "ok";

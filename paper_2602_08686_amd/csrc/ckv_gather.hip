@@ -14,6 +14,7 @@ struct GatherArgs {
   int64_t ks_b, ks_h, ks_t, vs_b, vs_h, vs_t;  // bytes
   int Hkv, T, cap;
   int lpr;        // lanes (16-byte pieces) per row
+  int shared;     // idx [Bz][cap] and count [Bz]: one index list for all KV heads of a batch element
   int row_bytes;
 };
 
@@ -21,14 +22,15 @@ constexpr int kGatherThreads = 256;
 
 __global__ void __launch_bounds__(kGatherThreads) gather_kernel(GatherArgs a) {
   const int unit = blockIdx.y;
-  const int n = min(a.count[unit], a.cap);
-  const int rows_per_block = kGatherThreads / a.lpr;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
+  const int list = a.shared ? b : unit;  // whose index list this unit follows
+  const int n = min(a.count[list], a.cap);
+  const int rows_per_block = kGatherThreads / a.lpr;
   const int piece = (threadIdx.x % a.lpr) * 16;
   const char *kb = a.k + b * a.ks_b + g * a.ks_h + piece, *vb = a.v + b * a.vs_b + g * a.vs_h + piece;
   // a few workgroups per unit stride over its kept rows (the count is far below cap in practice)
   for (int r = blockIdx.x * rows_per_block + threadIdx.x / a.lpr; r < n; r += gridDim.x * rows_per_block) {
-    const int t = a.idx[(size_t)unit * a.cap + r];
+    const int t = a.idx[(size_t)list * a.cap + r];
     if (t < 0 || t >= a.T) continue;
     const piece_t kk = *reinterpret_cast<const piece_t *>(kb + (int64_t)t * a.ks_t);
     const piece_t vv = *reinterpret_cast<const piece_t *>(vb + (int64_t)t * a.vs_t);
@@ -40,7 +42,7 @@ __global__ void __launch_bounds__(kGatherThreads) gather_kernel(GatherArgs a) {
 
 hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, const void *v,
                          const int32_t *idx, const int32_t *count, void *k_out, void *v_out,
-                         hipStream_t stream) {
+                         hipStream_t stream, bool shared_list) {
   GatherArgs a;
   a.k = (const char *)k;
   a.v = (const char *)v;
@@ -55,6 +57,7 @@ hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, con
   a.cap = p->cap;
   a.row_bytes = s.d * s.esize;
   a.lpr = a.row_bytes / 16;
+  a.shared = shared_list ? 1 : 0;
   const int rows_per_block = kGatherThreads / a.lpr;
   // enough workgroups to fill the chip, at most what cap rows need
   const int units = s.Bz * s.Hkv;

@@ -88,7 +88,15 @@ hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utili
                          hipStream_t stream);
 hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, const void *v,
                          const int32_t *idx, const int32_t *count, void *k_out, void *v_out,
-                         hipStream_t stream);
+                         hipStream_t stream, bool shared_list = false);
+// layer-shared mode (Alg. 1 as printed)
+hipError_t launch_alpha_accumulate(const Shape &s, const float *scores, float weight, float *alpha,
+                                   hipStream_t stream);
+hipError_t launch_risk_struct(const Shape &s, const float *alpha, const float *edges, int n_edges, float *risk,
+                              int32_t *bin, hipStream_t stream);
+hipError_t launch_shared_utility(const ckv_params *p, const Shape &s, const float *alpha, const float *rho,
+                                 const float *w_head, const float *t_gate, int n_ent, int n_ppl,
+                                 const int32_t *risk_bins, float *utility, float *tau, hipStream_t stream);
 
 }  // namespace ckv
 #endif

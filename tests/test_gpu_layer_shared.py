@@ -1,0 +1,103 @@
+"""GPU parity of the layer-shared mode (Alg. 1 as printed: one alpha per prompt, one index set per layer)
+through the C ABI, against the CPU oracle: stage by stage on the GPU's own intermediates (exact where
+integers or bytes are decided) and end to end within the score tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_08686_amd import binding as B
+from paper_2602_08686_amd import workloads as wl
+from parity_util import assert_index_sets_match, assert_scores_close, bits, f32, params_of
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _case(name, dtype, Bz, Hq, Hkv, d, T, W, n_layers, budget, **kw):
+    return wl.Workload(name, dtype, Bz, Hq, Hkv, d, T, W, wl.POOL_NONE, 1, budget, n_layers, seed=700 + T + W + Hq, **kw)
+
+
+CASES = [
+    _case("ls_gqa4", "bf16", 2, 8, 2, 128, 3000, 32, 3, 300, gate=True, pareto_frac=0.05),
+    _case("ls_mha_ragged", "bf16", 1, 4, 4, 128, 2501, 20, 2, 200, sink_scale=8.0),         # T % 4 != 0
+    _case("ls_f32", "f32", 2, 4, 2, 64, 1024, 32, 2, 128, gate=True, needles=3),
+]
+
+
+@pytest.mark.parametrize("w", CASES, ids=lambda w: w.name)
+def test_layer_shared_mode_matches_oracle(w):
+    print(f"case {w.name}", flush=True)
+    L, Bz, Hq, Hkv, T, W, P = w.n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.window, w.prefix
+    tabs = wl.make_tables(w, DEV)
+    layers = [wl.make_layer(w, l, DEV) for l in range(L)]
+    cap = w.cap   # rows per index list: the per-head calls' capacity rule holds the shared list as well
+    params = [params_of(w, t["q"], t["k"], t["v"], layer=l, flags=B.FLAG_VALUE_NORM) for l, t in enumerate(layers)]
+    buf = B.LayerBuffers(params[0], DEV)
+
+    # ---- (A) alpha: mean over layers and heads of the per-head window masses -------------------
+    alpha = torch.zeros(Bz, T, device=DEV)
+    rho = [torch.empty(Bz, Hkv, T, device=DEV) for _ in range(L)]
+    ref_maps = []
+    for l, t in enumerate(layers):
+        B.ckv_window_scores(params[l], t["q"], t["k"], t["v"], None, buf.scores, rho[l], buf.workspace)
+        B.ckv_alpha_accumulate(params[l], buf.scores, 1.0 / (L * Hq), alpha)
+        ref_maps.append(oracle.window_scores(f32(t["q"]), f32(t["k"])))
+    torch.cuda.synchronize()
+    ref_alpha = oracle.alpha_mean(ref_maps)
+    ga = alpha.cpu().numpy()
+    assert_scores_close(ga, ref_alpha, "alpha")
+    np.testing.assert_allclose(ga.astype(np.float64).sum(-1), T, rtol=2e-4)                 # Eq. 4: mean scale one
+
+    # ---- (A) structural risk and its bin ----------------------------------------------------------
+    edges = torch.linspace(0.0, float(np.log(T)), 19, device=DEV)                            # 20 bins
+    risk = torch.empty(Bz, device=DEV)
+    b_ent = torch.empty(Bz, dtype=torch.int32, device=DEV)
+    B.ckv_risk_struct(params[0], alpha, edges, risk, b_ent)
+    torch.cuda.synchronize()
+    gr = risk.cpu().numpy()
+    np.testing.assert_allclose(gr, oracle.risk_struct(ga.astype(np.float64)), rtol=1e-6)     # same alpha in
+    np.testing.assert_allclose(gr, oracle.risk_struct(ref_alpha), rtol=1e-3)                 # end to end
+    np.testing.assert_array_equal(b_ent.cpu().numpy(), oracle.discretize(gr, edges.cpu().numpy()))
+
+    # ---- (B)-(D) per layer --------------------------------------------------------------------------
+    one = B.make_params(batch=Bz, n_q_heads=1, n_kv_heads=1, head_dim=w.head_dim, seq_len=T, window=W,
+                        dtype=w.dtype, pool=wl.POOL_NONE, pool_kernel=1, budget=w.budget, cap=cap, n_layers=L)
+    util = torch.empty(Bz, P, device=DEV)
+    tau = torch.empty(Bz, device=DEV)
+    budget = torch.full((Bz, 1), w.budget, dtype=torch.int32, device=DEV)
+    idx = torch.full((Bz, cap), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(Bz, dtype=torch.int32, device=DEV)
+    bins = tabs.get("risk_bins")
+    for l, t in enumerate(layers):
+        B.ckv_shared_utility(params[l], alpha, rho[l], tabs["w_head"], tabs.get("t_gate"), tabs.get("n_ent", 0),
+                             tabs.get("n_ppl", 0), bins, util, tau)
+        idx.fill_(-1)   # entries at and beyond count are not written
+        B.ckv_select_topk(one, util, budget, tau, idx, cnt)
+        buf.k_out.zero_()
+        buf.v_out.zero_()
+        B.ckv_compact_kv_shared(params[l], t["k"], t["v"], idx, cnt, buf.k_out, buf.v_out)
+        torch.cuda.synchronize()
+        gu, gt, gi, gc = util.cpu().numpy(), tau.cpu().numpy(), idx.cpu().numpy(), cnt.cpu().numpy()
+        w_row = f32(tabs["w_head"][l])
+        # stage-exact: the oracle on the GPU's own alpha and rho
+        np.testing.assert_allclose(gu, oracle.shared_utility(ga.astype(np.float64), rho[l].cpu().numpy().astype(np.float64),
+                                                             w_row, W), rtol=3e-7, atol=0)
+        gate = tabs.get("t_gate")
+        ref_tau = np.zeros(Bz, np.float32) if gate is None else np.array(
+            [oracle.tau(f32(gate[l]), *bins.cpu().numpy()[b]) for b in range(Bz)], np.float32)
+        np.testing.assert_array_equal(gt, ref_tau)
+        oi, oc = oracle.select(gu[:, None, :], gt, budget.cpu().numpy(), W, cap)
+        np.testing.assert_array_equal(gc, oc[:, 0])
+        np.testing.assert_array_equal(gi, oi[:, 0])
+        np.testing.assert_array_equal(bits(buf.k_out), oracle.gather_shared(bits(t["k"]), gi, gc))
+        np.testing.assert_array_equal(bits(buf.v_out), oracle.gather_shared(bits(t["v"]), gi, gc))
+        # end to end: the oracle's own alpha, rho and selection
+        ref = oracle.layer_shared_layer(ref_alpha, bits(t["k"]), bits(t["v"]), f32(t["v"]), W=W, B_layer=w.budget, cap=cap,
+                                        w_head_row=w_row, gate_layer=None if gate is None else f32(gate[l]),
+                                        risk_bins=None if gate is None else bins.cpu().tolist())
+        assert_scores_close(gu, ref["utility"].astype(np.float64), "shared utility")
+        assert_index_sets_match(gi[:, None, :], gc[:, None], ref["idx"][:, None, :], ref["count"][:, None],
+                                ref["utility"][:, None, :], ref["tau"], budget.cpu().numpy(), W)
+        for b in range(Bz):
+            assert gi[b, gc[b] - W:gc[b]].tolist() == list(range(P, T))                      # window kept, last
