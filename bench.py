@@ -93,6 +93,70 @@ def cpu_baseline(w, layer_t, tables, n_batch: int, value_norm: bool) -> dict:
             "ms_per_layer_scaled": dt * 1e3 * w.batch / n_batch}
 
 
+def layer_shared_bench(args, w, n_layers, torch, B, wl) -> int:
+    """The paper-literal mode: phase A over all layers (scan with value norms, alpha accumulation, risk),
+    phase B over all layers (shared utility, selection, shared gather). One step = both phases."""
+    dev = "cuda"
+    tables = wl.make_tables(w, dev)
+    layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
+    q0, k0, v0 = layers[0]["q"], layers[0]["k"], layers[0]["v"]
+    params = [B.params_for(q0, k0, v0, pool=w.pool, pool_kernel=w.pool_kernel, budget=w.budget, cap=w.cap,
+                           layer=l % w.n_layers, n_layers=w.n_layers, flags=B.FLAG_VALUE_NORM) for l in range(n_layers)]
+    one = B.make_params(batch=w.batch, n_q_heads=1, n_kv_heads=1, head_dim=w.head_dim, seq_len=w.seq_len,
+                        window=w.window, dtype=w.dtype, pool=wl.POOL_NONE, pool_kernel=1, budget=w.budget, cap=w.cap,
+                        n_layers=w.n_layers)
+    buf = B.LayerBuffers(params[0], dev)
+    Bz, T, P = w.batch, w.seq_len, w.prefix
+    alpha = torch.zeros(Bz, T, device=dev)
+    rho = [torch.empty(Bz, w.n_kv_heads, T, device=dev) for _ in range(n_layers)]
+    risk, b_ent = torch.empty(Bz, device=dev), torch.empty(Bz, dtype=torch.int32, device=dev)
+    edges = torch.linspace(0.0, float(torch.log(torch.tensor(float(T)))), 19, device=dev)
+    util, tau = torch.empty(Bz, P, device=dev), torch.empty(Bz, device=dev)
+    budget = torch.full((Bz, 1), w.budget, dtype=torch.int32, device=dev)
+    idx = torch.full((Bz, w.cap), -1, dtype=torch.int32, device=dev)
+    cnt = torch.empty(Bz, dtype=torch.int32, device=dev)
+    wgt = 1.0 / (n_layers * w.n_q_heads)
+
+    def step():
+        alpha.zero_()
+        for l in range(n_layers):
+            t = layers[l]
+            B.ckv_window_scores(params[l], t["q"], t["k"], t["v"], None, buf.scores, rho[l], buf.workspace)
+            B.ckv_alpha_accumulate(params[l], buf.scores, wgt, alpha)
+        B.ckv_risk_struct(params[0], alpha, edges, risk, b_ent)
+        for l in range(n_layers):
+            t = layers[l]
+            B.ckv_shared_utility(params[l], alpha, rho[l], tables["w_head"], None, 0, 0, None, util, tau)
+            B.ckv_select_topk(one, util, budget, tau, idx, cnt)
+            B.ckv_compact_kv_shared(params[l], t["k"], t["v"], idx, cnt, buf.k_out, buf.v_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_layer = ms_per_step / n_layers
+    kept = int(cnt.sum().item()) * w.n_kv_heads
+    layer_bytes = algorithmic_bytes(w, kept, True)
+    value = layer_bytes / (ms_per_layer * 1e-3) / 1e9
+    out = {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) of prefill-end scan+select+gather; ms/layer beside it",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_layer": round(ms_per_layer, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "mode": "layer_shared (Alg. 1 as printed)", "layers_per_step": n_layers,
+                   "batch": w.batch, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "seq_len": w.seq_len, "window": w.window, "budget_per_layer": w.budget, "value_norm": True,
+                   "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
+        "roofline": None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +171,9 @@ def main() -> int:
     ap.add_argument("--unfused", action="store_true",
                     help="ckv_window_scores + ckv_apply_tables instead of ckv_window_utility (materialises the "
                          "per-head window mass)")
+    ap.add_argument("--mode", default="per_head", choices=["per_head", "layer_shared"],
+                    help="per_head: the north-star path (default). layer_shared: the paper's Alg. 1 as printed, one "
+                         "alpha per prompt and one index set per layer (reported with the same metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=0, help="batch elements in the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -133,6 +200,8 @@ def main() -> int:
     flags = B.FLAG_VALUE_NORM if args.value_norm else 0
     flags |= B.FLAG_SCAN_SINGLE_READ if args.scan == "single_read" else B.FLAG_SCAN_TWO_KERNELS
 
+    if args.mode == "layer_shared":
+        return layer_shared_bench(args, w, n_layers, torch, B, wl)
     tables = wl.make_tables(w, dev)
     layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
     q0, k0, v0 = layers[0]["q"], layers[0]["k"], layers[0]["v"]

@@ -130,6 +130,35 @@ def test_window_utility_and_scan_flags_are_validated_on_the_host():
     assert B.ckv_scan_status_offset(both) == -1
 
 
+def test_layer_shared_entry_points_are_validated_on_the_host():
+    lib = B.load()
+    p = _good()
+    ref = ctypes.byref
+    d = ctypes.c_void_p(256)
+    f = ctypes.c_float
+    assert lib.ckv_alpha_accumulate(ref(p), None, f(0.5), d, None) == B.CKV_EINVAL
+    assert lib.ckv_alpha_accumulate(ref(p), d, f(0.5), None, None) == B.CKV_EINVAL
+    assert lib.ckv_alpha_accumulate(ref(p), d, f(float("nan")), d, None) == B.CKV_EINVAL
+    assert lib.ckv_alpha_accumulate(None, d, f(0.5), d, None) == B.CKV_EINVAL
+    assert lib.ckv_risk_struct(ref(p), None, None, 0, d, None, None) == B.CKV_EINVAL
+    assert lib.ckv_risk_struct(ref(p), d, None, 0, None, None, None) == B.CKV_EINVAL
+    assert lib.ckv_risk_struct(ref(p), d, None, -1, d, None, None) == B.CKV_EINVAL
+    assert lib.ckv_risk_struct(ref(p), d, None, 19, d, d, None) == B.CKV_EINVAL      # bins asked for, no edges
+    su = lambda **kw: lib.ckv_shared_utility(ref(p), kw.get("alpha", d), kw.get("rho", d), kw.get("w_head", d),
+                                             kw.get("t_gate"), kw.get("n_ent", 0), kw.get("n_ppl", 0), kw.get("bins"),
+                                             kw.get("util", d), kw.get("tau", d), None)
+    for name in ("alpha", "rho", "w_head", "util", "tau"):
+        assert su(**{name: None}) == B.CKV_EINVAL
+    assert su(t_gate=d, n_ent=20, n_ppl=4) == B.CKV_EINVAL                          # gate without risk bins
+    assert su(t_gate=d, n_ent=0, n_ppl=4, bins=d) == B.CKV_EINVAL
+    args = [d] * 6
+    for i in range(6):
+        bad = list(args)
+        bad[i] = None
+        assert lib.ckv_compact_kv_shared(ref(p), *bad, None) == B.CKV_EINVAL
+    assert lib.ckv_compact_kv_shared(ref(_good(window=0)), *args, None) == B.CKV_EINVAL
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         B.load(tmp_path / "libckv.so")

@@ -101,3 +101,55 @@ def test_layer_shared_mode_matches_oracle(w):
                                 ref["utility"][:, None, :], ref["tau"], budget.cpu().numpy(), W)
         for b in range(Bz):
             assert gi[b, gc[b] - W:gc[b]].tolist() == list(range(P, T))                      # window kept, last
+
+
+def test_layer_shared_full_size_two_layers_of_c3():
+    """C3's shapes (the launch configuration the benchmark times), two layers, two batch elements against
+    the oracle element by element; properties on all."""
+    w = wl.C3
+    L, Bz, Hq, Hkv, T, W, P, G = 2, w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.window, w.prefix, w.group
+    tabs = wl.make_tables(w, DEV)
+    layers = [wl.make_layer(w, l, DEV) for l in range(L)]
+    params = [params_of(w, t["q"], t["k"], t["v"], layer=l, flags=B.FLAG_VALUE_NORM) for l, t in enumerate(layers)]
+    buf = B.LayerBuffers(params[0], DEV)
+    alpha = torch.zeros(Bz, T, device=DEV)
+    rho = [torch.empty(Bz, Hkv, T, device=DEV) for _ in range(L)]
+    for l, t in enumerate(layers):
+        B.ckv_window_scores(params[l], t["q"], t["k"], t["v"], None, buf.scores, rho[l], buf.workspace)
+        B.ckv_alpha_accumulate(params[l], buf.scores, 1.0 / (L * Hq), alpha)
+    risk = torch.empty(Bz, device=DEV)
+    B.ckv_risk_struct(params[0], alpha, None, risk)
+    torch.cuda.synchronize()
+    ga = alpha.cpu().numpy()
+    np.testing.assert_allclose(ga.astype(np.float64).sum(-1), T, rtol=2e-4)
+    np.testing.assert_allclose(risk.cpu().numpy(), oracle.risk_struct(ga.astype(np.float64)), rtol=1e-6)
+    assert (risk.cpu().numpy() <= np.log(T)).all()                                   # entropy of T outcomes
+    sample = [0, 9]
+    ref_alpha = {b: oracle.alpha_mean([oracle.window_scores(f32(t["q"][b:b + 1]), f32(t["k"][b:b + 1])) for t in layers])
+                 for b in sample}
+    for b in sample:
+        assert_scores_close(ga[b:b + 1], ref_alpha[b], f"alpha of batch element {b}")
+    one = B.make_params(batch=Bz, n_q_heads=1, n_kv_heads=1, head_dim=w.head_dim, seq_len=T, window=W, dtype=w.dtype,
+                        pool=wl.POOL_NONE, pool_kernel=1, budget=w.budget, cap=w.cap, n_layers=w.n_layers)
+    util, tau = torch.empty(Bz, P, device=DEV), torch.empty(Bz, device=DEV)
+    budget = torch.full((Bz, 1), w.budget, dtype=torch.int32, device=DEV)
+    idx = torch.full((Bz, w.cap), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(Bz, dtype=torch.int32, device=DEV)
+    l, t = 1, layers[1]
+    B.ckv_shared_utility(params[l], alpha, rho[l], tabs["w_head"], None, 0, 0, None, util, tau)
+    B.ckv_select_topk(one, util, budget, tau, idx, cnt)
+    B.ckv_compact_kv_shared(params[l], t["k"], t["v"], idx, cnt, buf.k_out, buf.v_out)
+    torch.cuda.synchronize()
+    gu, gi, gc = util.cpu().numpy(), idx.cpu().numpy(), cnt.cpu().numpy()
+    assert (gc == w.budget).all()                                                    # 512 of 32768: 1.56 % (Table A6)
+    oi, oc = oracle.select(gu[:, None, :], tau.cpu().numpy(), budget.cpu().numpy(), W, w.cap)
+    np.testing.assert_array_equal(gi, oi[:, 0])
+    np.testing.assert_array_equal(bits(buf.k_out), oracle.gather_shared(bits(t["k"]), gi, gc))
+    np.testing.assert_array_equal(bits(buf.v_out), oracle.gather_shared(bits(t["v"]), gi, gc))
+    w_row = f32(tabs["w_head"][l])
+    for b in sample:
+        ref = oracle.layer_shared_layer(ref_alpha[b], bits(t["k"][b:b + 1]), bits(t["v"][b:b + 1]), f32(t["v"][b:b + 1]),
+                                        W=W, B_layer=w.budget, cap=w.cap, w_head_row=w_row)
+        assert_scores_close(gu[b:b + 1], ref["utility"].astype(np.float64), f"shared utility of batch element {b}")
+        assert_index_sets_match(gi[b:b + 1, None, :], gc[b:b + 1, None], ref["idx"][:, None, :], ref["count"][:, None],
+                                ref["utility"][:, None, :], ref["tau"], budget.cpu().numpy()[b:b + 1], W)
