@@ -162,7 +162,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--config", default="c3",
+                    choices=["c1", "c2", "c3", "c4", "c5", "s16k_b256", "s32k_b512", "s64k_b1024", "s128k_b2048", "s32k_b128"],
+                    help="c3 is the workload the metric is quoted on; s*: length scaling at a fixed retained ratio "
+                         "and the 128-token budget (C3's attention shape, batch 4)")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffers (0 = the config's depth)")
     ap.add_argument("--value-norm", action="store_true")
     ap.add_argument("--given-lse", action="store_true", help="caller-supplied LSE: single pass over K")
@@ -195,7 +198,7 @@ def main() -> int:
         return 3
     torch.cuda.set_device(0)
     dev = "cuda"
-    w = {c.name[:2]: c for c in wl.CONFIGS}[args.config]
+    w = ({c.name[:2]: c for c in wl.CONFIGS} | {c.name.split("_gqa")[0]: c for c in wl.SWEEP})[args.config]
     n_layers = args.layers or w.n_layers
     flags = B.FLAG_VALUE_NORM if args.value_norm else 0
     flags |= B.FLAG_SCAN_SINGLE_READ if args.scan == "single_read" else B.FLAG_SCAN_TWO_KERNELS
@@ -257,7 +260,22 @@ def main() -> int:
             c.record()
             pairs1.append((a, b_))
             pairs2.append((b_, c))
+    pairs3, pairs4 = [], []
+    for _ in range(reps):
+        for l in range(n_layers):
+            t = layers[l]
+            a, b_, c = ev(), ev(), ev()
+            a.record()
+            B.ckv_select_topk(params[l], buf.utility, buf.budget, buf.tau, buf.idx, buf.count, buf.workspace)
+            b_.record()
+            B.ckv_compact_kv(params[l], t["k"], t["v"], buf.idx, buf.count, buf.k_out, buf.v_out)
+            c.record()
+            pairs3.append((a, b_))
+            pairs4.append((b_, c))
     torch.cuda.synchronize()
+    ms_select = sum(a.elapsed_time(b_) for a, b_ in pairs3) / len(pairs3)
+    ms_gather = sum(a.elapsed_time(b_) for a, b_ in pairs4) / len(pairs4)
+    gather_bytes = 4 * kept * w.head_dim * (2 if w.dtype == "bf16" else 4)
     ms_pass1 = sum(a.elapsed_time(b_) for a, b_ in pairs1) / len(pairs1)
     ms_pass2 = sum(a.elapsed_time(b_) for a, b_ in pairs2) / len(pairs2)
     bf16 = w.dtype == "bf16"
@@ -288,6 +306,8 @@ def main() -> int:
         "traffic": measured_traffic(dominant) if args.config == "c3" and not args.value_norm else None,
         "ms_per_launch": round(dom_ms, 4),
         "scan_ms": scan_ms,
+        "select_ms": round(ms_select, 4), "gather_ms": round(ms_gather, 4),
+        "gather_gbs": round(gather_bytes / (ms_gather * 1e-3) / 1e9, 1),
         "mfma_tflops": {"rowstats": round(scan_flops(w) / (ms_pass1 * 1e-3) / 1e12, 1),
                         "colsum": round(scan_flops(w) / (ms_pass2 * 1e-3) / 1e12, 1),  # fused: its fix-up kernel included
                         "peak": MFMA_BF16_PEAK_TFLOPS},

@@ -204,6 +204,11 @@ ckv_status ckv_window_utility(const ckv_params *params, const void *q_win, const
  *   tau      in   [Bz] fp32                       on the device)
  *   idx      out  [Bz,Hkv,cap] int32; entries at and beyond count[b,g] are not written
  *   count    out  [Bz,Hkv] int32
+ *   workspace     optional (NULL allowed). Up to 65536 prefix positions it is not used. Beyond that,
+ *                 with ckv_workspace_bytes(params) bytes (256-byte aligned; CKV_EWORKSPACE if
+ *                 misaligned or smaller) a unit's positions are split over several workgroups, which is
+ *                 several times faster for long contexts with few (batch, head) units; the result is
+ *                 the same either way. Contents on entry are ignored.
  */
 ckv_status ckv_select_topk(const ckv_params *params, const float *utility, const int32_t *budget,
                            const float *tau, int32_t *idx, int32_t *count, void *workspace,

@@ -110,6 +110,9 @@ void layout(const ckv_params *p, const Shape &s, Workspace *w) {
   w->fpart_off = off;
   w->fpart_bytes = s.fused_ok ? (size_t)2 * kFusedGridMax * s.NQ * kTile * sizeof(float2) : 0;
   off = align256(off + w->fpart_bytes);
+  w->select_off = off;
+  w->select_bytes = select_workspace_bytes(s);
+  off = align256(off + w->select_bytes);
   w->total = off;
 }
 
@@ -264,11 +267,16 @@ extern "C" ckv_status ckv_select_topk(const ckv_params *params, const float *uti
   ckv_status st = validate(params);
   if (st != CKV_OK) return st;
   if (!utility || !budget || !tau || !idx || !count) return CKV_EINVAL;
-  (void)workspace;  // the selection keeps its histograms in LDS; the argument is reserved
-  (void)workspace_bytes;
   Shape s;
   derive(params, &s);
-  if (launch_select(params, s, utility, budget, tau, idx, count, (hipStream_t)hip_stream) != hipSuccess)
+  // Optional: up to 65536 prefix positions the selection keeps everything on chip; beyond that a
+  // workspace lets it split a unit over several workgroups.
+  Workspace w;
+  layout(params, s, &w);
+  const bool split = workspace && w.select_bytes > 0;
+  if (split && workspace_ok(w, workspace, workspace_bytes) != CKV_OK) return CKV_EWORKSPACE;
+  if (launch_select(params, s, utility, budget, tau, idx, count, split ? (char *)workspace + w.select_off : nullptr,
+                    (hipStream_t)hip_stream) != hipSuccess)
     return CKV_EHIP;
   return CKV_OK;
 }

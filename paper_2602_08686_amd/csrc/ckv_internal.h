@@ -45,6 +45,7 @@ struct Workspace {
   size_t vsum_off, vsum_bytes;   // float  [units][vnorm blocks] partial sums of value norms
   size_t sync_off, sync_bytes;   // uint32 synchronisation words of the single-read scan
   size_t fpart_off, fpart_bytes; // float2 [2][workgroups][NQ*32] row partials of the single-read scan
+  size_t select_off, select_bytes;  // int: the split selection's merged histograms, slice counts, thresholds
   size_t total;
 };
 void layout(const ckv_params *p, const Shape &s, Workspace *w);
@@ -83,9 +84,12 @@ hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float 
                                const float *vnorm_ratio, const float *w_head, const float *head_share,
                                const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,
                                float *utility, int32_t *budget, float *tau, hipStream_t stream);
+// ws: nullptr, or select_workspace_bytes(s) bytes (256-byte aligned) that let long prefixes be split
+// over several workgroups per unit; the result is the same either way.
+size_t select_workspace_bytes(const Shape &s);
 hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utility,
                          const int32_t *budget, const float *tau, int32_t *idx, int32_t *count,
-                         hipStream_t stream);
+                         char *ws, hipStream_t stream);
 hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, const void *v,
                          const int32_t *idx, const int32_t *count, void *k_out, void *v_out,
                          hipStream_t stream, bool shared_list = false);

@@ -116,12 +116,115 @@ __device__ __forceinline__ void digit_histogram(int *hist, const uint32_t (&key)
   }
 }
 
+// Scratch of ranked_write, in LDS.
+template <int NV>
+struct RankScratch {
+  static constexpr int N = NV * (kSelectThreads / kWave);
+  int wave_tot[N];             // per (block of 4096 positions, wave): kept-above count | equal count << 16
+  int pre_gt[N + 1], pre_eq[N + 1];  // their exclusive prefixes, unpacked, then the totals
+};
+struct BlockTotals {
+  int gt, eq;  // keys above / equal to the threshold among the workgroup's positions
+};
+
+// Writes the kept positions of the workgroup's NV * 4096 positions (thread tid holds positions
+// t_base + 4 * (j * 1024 + tid) + e) in ascending order: every key above thr, and the first need_eq keys
+// equal to it, at the rank they have among all kept positions. base_gt / base_eq count the keys above /
+// equal that lie before t_base; ranks at or beyond kp are dropped. All threads of the workgroup call it.
+template <int NV>
+__device__ __forceinline__ BlockTotals ranked_write(const uint32_t (&key)[NV][4], uint32_t thr, int need_eq, int kp,
+                                                    int base_gt, int base_eq, int t_base, int32_t *out,
+                                                    RankScratch<NV> &rs, int tid, int lane, int wave) {
+  constexpr int NW = kSelectThreads / kWave;
+  int *wave_tot = rs.wave_tot, *pre_gt = rs.pre_gt, *pre_eq = rs.pre_eq;
+  // Ranks in position order: block j, then wave, then lane, then element. Counts travel packed as
+  // (above | equal << 16); a wave covers 256 positions, so neither half overflows.
+  auto own_count = [&](int j) {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c += (key[j][e] > thr ? 1 : 0) + (key[j][e] == thr ? 0x10000 : 0);
+    return c;
+  };
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int c = own_count(j);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+    if (lane == 0) wave_tot[j * NW + wave] = c;
+  }
+  __syncthreads();
+  // exclusive prefix over the (block, wave) totals in position order, by wave 0; the grand totals
+  // end up behind the last entry
+  if (wave == 0) {
+    constexpr int PER = (NV * NW + kWave - 1) / kWave;
+    int g[PER], q[PER], sg = 0, sq = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int i = lane * PER + e;
+      const int c = i < NV * NW ? wave_tot[i] : 0;
+      g[e] = c & 0xffff;
+      q[e] = c >> 16;
+      sg += g[e];
+      sq += q[e];
+    }
+    int ig = sg, iq = sq;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int ug = __shfl_up(ig, o), uq = __shfl_up(iq, o);
+      if (lane >= o) {
+        ig += ug;
+        iq += uq;
+      }
+    }
+    int rg = ig - sg, rq = iq - sq;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int i = lane * PER + e;
+      if (i < NV * NW) {
+        pre_gt[i] = rg;
+        pre_eq[i] = rq;
+      }
+      rg += g[e];
+      rq += q[e];
+    }
+    if (lane == 63) {
+      pre_gt[NV * NW] = ig;
+      pre_eq[NV * NW] = iq;
+    }
+  }
+  __syncthreads();
+  const int tot_gt = pre_gt[NV * NW], tot_eq = pre_eq[NV * NW];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int own = own_count(j);
+    int incl = own;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    const int before = incl - own;
+    int gt_before = base_gt + pre_gt[j * NW + wave] + (before & 0xffff);
+    int eq_before = base_eq + pre_eq[j * NW + wave] + (before >> 16);
+    const int t = 4 * (j * kSelectThreads + tid);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool gt = key[j][e] > thr, eq = key[j][e] == thr;
+      if (gt || (eq && eq_before < need_eq)) {
+        const int pos = gt_before + min(eq_before, need_eq);
+        if (pos < kp) out[pos] = t_base + t + e;
+      }
+      gt_before += gt;
+      eq_before += eq;
+    }
+  }
+  return BlockTotals{tot_gt, tot_eq};
+}
+
 template <int NV>
 __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a) {
-  constexpr int NW = kSelectThreads / kWave;
   __shared__ int hist[2048];
-  __shared__ int wave_tot[NV * NW];  // per (block of 4096 positions, wave): kept-above count | equal count << 16
-  __shared__ int pre_gt[NV * NW + 1], pre_eq[NV * NW + 1];  // their exclusive prefixes, unpacked, then the totals
+  __shared__ RankScratch<NV> ranks;
   __shared__ uint32_t s_prefix;
   __shared__ int s_k, s_state;  // s_state: 0 = keep all candidates, 1 = select, 2 = keep none
 
@@ -205,90 +308,186 @@ __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a
     need_eq = s_k;
   }
 
-  // Ranks in position order: block j, then wave, then lane, then element. Counts travel packed as
-  // (above | equal << 16); a wave covers 256 positions, so neither half overflows.
-  auto own_count = [&](int j) {
-    int c = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) c += (key[j][e] > thr ? 1 : 0) + (key[j][e] == thr ? 0x10000 : 0);
-    return c;
-  };
-#pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    int c = own_count(j);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
-    if (lane == 0) wave_tot[j * NW + wave] = c;
-  }
-  __syncthreads();
-  // exclusive prefix over the (block, wave) totals in position order, by wave 0; the grand totals
-  // end up behind the last entry
-  if (wave == 0) {
-    constexpr int PER = (NV * NW + kWave - 1) / kWave;
-    int g[PER], q[PER], sg = 0, sq = 0;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int i = lane * PER + e;
-      const int c = i < NV * NW ? wave_tot[i] : 0;
-      g[e] = c & 0xffff;
-      q[e] = c >> 16;
-      sg += g[e];
-      sq += q[e];
-    }
-    int ig = sg, iq = sq;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int ug = __shfl_up(ig, o), uq = __shfl_up(iq, o);
-      if (lane >= o) {
-        ig += ug;
-        iq += uq;
-      }
-    }
-    int rg = ig - sg, rq = iq - sq;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int i = lane * PER + e;
-      if (i < NV * NW) {
-        pre_gt[i] = rg;
-        pre_eq[i] = rq;
-      }
-      rg += g[e];
-      rq += q[e];
-    }
-    if (lane == 63) {
-      pre_gt[NV * NW] = ig;
-      pre_eq[NV * NW] = iq;
-    }
-  }
-  __syncthreads();
-  const int tot_gt = pre_gt[NV * NW], tot_eq = pre_eq[NV * NW];
   int32_t *out = a.idx + (size_t)unit * a.cap;
-#pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const int own = own_count(j);
-    int incl = own;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
-    }
-    const int before = incl - own;
-    int gt_before = pre_gt[j * NW + wave] + (before & 0xffff), eq_before = pre_eq[j * NW + wave] + (before >> 16);
-    const int t = 4 * (j * kSelectThreads + tid);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const bool gt = key[j][e] > thr, eq = key[j][e] == thr;
-      if (gt || (eq && eq_before < need_eq)) {
-        const int pos = gt_before + min(eq_before, need_eq);
-        if (pos < kp) out[pos] = t + e;
-      }
-      gt_before += gt;
-      eq_before += eq;
-    }
-  }
+  const BlockTotals tot = ranked_write<NV>(key, thr, need_eq, kp, 0, 0, 0, out, ranks, tid, lane, wave);
+  const int tot_gt = tot.gt, tot_eq = tot.eq;
   const int kept = min(tot_gt + min(tot_eq, need_eq), kp);
   for (int j = tid; j < W; j += kSelectThreads) out[kept + j] = P + j;
   if (tid == 0) a.count[unit] = kept + W;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Split select: prefixes beyond the register kernel's 65536 positions, when the caller passes a
+// workspace. A unit's positions are cut into slices of 8192, one workgroup each, so that long contexts
+// with few (batch, head) units still fill the chip. Five launches walk the same steps as the register
+// kernel: three digit histograms (slices merge theirs into the unit's histogram in global memory with
+// integer atomics: order-independent, so the result is deterministic), the slices' counts of keys above
+// / equal to the threshold, and the ranked write. Every workgroup derives the threshold digits from
+// the merged histograms itself (4096 integers per unit), which saves the launches in between.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSplitNV = 2;
+constexpr int kSplitSlice = kSplitNV * 4 * kSelectThreads;  // positions per workgroup
+constexpr int kSplitHist = 2048 + 1024 + 1024;              // merged histogram words per unit
+
+struct SplitArgs {
+  SelectArgs a;
+  int *hist;       // [units][kSplitHist], zero before the first phase
+  int *slice_cnt;  // [units][S] keys above | equal << 16 of each slice
+  int *thr;        // [units][4] threshold key, need_eq
+  int S;           // slices per unit
+};
+
+__global__ void __launch_bounds__(kSelectThreads) select_split_zero_kernel(int *words, int n) {
+  const int i = blockIdx.x * kSelectThreads + threadIdx.x;
+  if (i < n) words[i] = 0;
+}
+
+// PHASE 0..2: histogram of digit PHASE (11, 10, 10 bits from the top) among the keys that match the
+// digits found so far. PHASE 3: per-slice counts and the unit's threshold. PHASE 4: ranked write.
+template <int PHASE>
+__global__ void __launch_bounds__(kSelectThreads) select_split_kernel(SplitArgs sa) {
+  __shared__ int hist[2048];
+  __shared__ RankScratch<kSplitNV> ranks;
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_k, s_state;  // s_state: 0 = keep all candidates, 1 = select, 2 = keep none
+  __shared__ int s_red[kSelectThreads / kWave];
+
+  const SelectArgs &a = sa.a;
+  const int unit = blockIdx.x / sa.S, slice = blockIdx.x % sa.S;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int P = a.P, W = a.W;
+  const float *u = a.utility + (size_t)unit * P;
+  const float tau = a.tau[unit / a.Hkv];
+  int bud = a.budget[unit];
+  bud = max(W, min(bud, min(a.cap, a.T)));
+  const int kp = bud - W;
+  const int t_base = slice * kSplitSlice;
+  int *gh = sa.hist + (size_t)unit * kSplitHist;
+
+  uint32_t key[kSplitNV][4];
+#pragma unroll
+  for (int j = 0; j < kSplitNV; ++j) {
+    const int t = t_base + 4 * (j * kSelectThreads + tid);
+    f32x4_sel x = {-1.0f, -1.0f, -1.0f, -1.0f};
+    if (t < P) x = *reinterpret_cast<const f32x4_sel *>(u + t);  // P % 4 == 0: whole vectors only
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float xe = x[e];
+      key[j][e] = (t < P && xe >= tau) ? key_of(xe) + 1u : 0u;
+    }
+  }
+
+  // Threshold digits from the histograms merged by the earlier phases (same arithmetic in every
+  // workgroup of the unit).
+  int state = 1, k = max(kp, 1);
+  uint32_t prefix = 0u;
+  if constexpr (PHASE >= 1 && PHASE <= 3) {
+    for (int i = tid; i < 2048; i += kSelectThreads) hist[i] = gh[i];
+    __syncthreads();
+    if (wave == 0) {
+      const BinResult r = find_bin<2048>(hist, max(kp, 1), lane);
+      if (lane == 0) {
+        s_prefix = (uint32_t)max(r.bin, 0);
+        s_k = kp - r.above;
+        s_state = r.total <= kp ? 0 : (kp == 0 ? 2 : 1);
+      }
+    }
+    __syncthreads();
+    state = s_state;
+    prefix = s_prefix;
+    k = s_k;
+#pragma unroll
+    for (int level = 1; level <= 2; ++level) {
+      if (PHASE > level && state == 1) {
+        __syncthreads();  // everyone has read s_prefix / s_k and wave 0 is done with hist
+        hist[tid] = gh[2048 + 1024 * (level - 1) + tid];
+        __syncthreads();
+        if (wave == 0) {
+          const BinResult r = find_bin<1024>(hist, k, lane);
+          if (lane == 0) {
+            s_prefix = (prefix << 10) | (uint32_t)r.bin;
+            s_k = k - r.above;
+          }
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        k = s_k;
+      }
+    }
+  }
+
+  if constexpr (PHASE <= 2) {
+    if (PHASE > 0 && state != 1) return;
+    constexpr int NB = PHASE == 0 ? 2048 : 1024;
+    __syncthreads();
+    for (int i = tid; i < NB; i += kSelectThreads) hist[i] = 0;
+    __syncthreads();
+    digit_histogram<kSplitNV, 20 - 10 * PHASE, PHASE == 0 ? 11 : 10, false>(hist, key, prefix, lane);
+    __syncthreads();
+    int *g = gh + (PHASE == 0 ? 0 : 2048 + 1024 * (PHASE - 1));
+    for (int i = tid; i < NB; i += kSelectThreads) {
+      const int h = hist[i];
+      if (h) atomicAdd(&g[i], h);
+    }
+    return;
+  }
+
+  if constexpr (PHASE == 3) {
+    uint32_t thr = 0u;  // keep-all: every candidate has k' > 0
+    int need_eq = 0;
+    if (state == 2) thr = 0xffffffffu;
+    else if (state == 1) {
+      thr = prefix;
+      need_eq = k;
+    }
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < kSplitNV; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) c += (key[j][e] > thr ? 1 : 0) + (key[j][e] == thr ? 0x10000 : 0);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);  // 256 positions a wave: neither half overflows
+    if (lane == 0) s_red[wave] = c;
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;  // 8192 positions a slice: neither half overflows
+      for (int w = 0; w < kSelectThreads / kWave; ++w) tot += s_red[w];
+      sa.slice_cnt[(size_t)unit * sa.S + slice] = tot;
+      if (slice == 0) {
+        sa.thr[unit * 4 + 0] = (int)thr;
+        sa.thr[unit * 4 + 1] = need_eq;
+      }
+    }
+    return;
+  }
+
+  if constexpr (PHASE == 4) {
+    const uint32_t thr = (uint32_t)sa.thr[unit * 4 + 0];
+    const int need_eq = sa.thr[unit * 4 + 1];
+    int base_gt = 0, base_eq = 0, all_gt = 0, all_eq = 0;
+    for (int i = 0; i < sa.S; ++i) {  // same address in every lane: one broadcast load each
+      const int c = sa.slice_cnt[(size_t)unit * sa.S + i];
+      if (i < slice) {
+        base_gt += c & 0xffff;
+        base_eq += c >> 16;
+      }
+      all_gt += c & 0xffff;
+      all_eq += c >> 16;
+    }
+    int32_t *out = a.idx + (size_t)unit * a.cap;
+    ranked_write<kSplitNV>(key, thr, need_eq, kp, base_gt, base_eq, t_base, out, ranks, tid, lane, wave);
+    if (slice == 0) {
+      const int kept = min(all_gt + min(all_eq, need_eq), kp);
+      for (int j = tid; j < W; j += kSelectThreads) out[kept + j] = P + j;
+      if (tid == 0) a.count[unit] = kept + W;
+    }
+  }
+}
+
+size_t select_workspace_bytes(const Shape &s) {
+  if (s.P <= 16 * 4 * kSelectThreads || s.P % 4 != 0) return 0;  // the register kernel or the streaming one
+  const size_t units = (size_t)s.Bz * s.Hkv, S = (s.P + kSplitSlice - 1) / kSplitSlice;
+  return units * (kSplitHist + S + 4) * sizeof(int);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -448,7 +647,7 @@ __global__ void __launch_bounds__(kSelectThreads) select_kernel(SelectArgs a) {
 
 hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utility,
                          const int32_t *budget, const float *tau, int32_t *idx, int32_t *count,
-                         hipStream_t stream) {
+                         char *ws, hipStream_t stream) {
   SelectArgs a;
   a.utility = utility;
   a.budget = budget;
@@ -465,7 +664,24 @@ hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utili
   else if (aligned && vectors <= 4) hipLaunchKernelGGL(select_reg_kernel<4>, grid, block, 0, stream, a);
   else if (aligned && vectors <= 8) hipLaunchKernelGGL(select_reg_kernel<8>, grid, block, 0, stream, a);
   else if (aligned && vectors <= 16) hipLaunchKernelGGL(select_reg_kernel<16>, grid, block, 0, stream, a);
-  else hipLaunchKernelGGL(select_kernel, grid, block, 0, stream, a);
+  else if (aligned && ws && select_workspace_bytes(s) > 0) {
+    SplitArgs sa;
+    sa.a = a;
+    sa.S = (s.P + kSplitSlice - 1) / kSplitSlice;
+    const size_t units = (size_t)s.Bz * s.Hkv;
+    sa.hist = reinterpret_cast<int *>(ws);
+    sa.slice_cnt = sa.hist + units * kSplitHist;
+    sa.thr = sa.slice_cnt + units * sa.S;
+    const int n_zero = (int)(units * kSplitHist);
+    const dim3 split_grid((unsigned)(units * sa.S));
+    hipLaunchKernelGGL(select_split_zero_kernel, dim3((n_zero + kSelectThreads - 1) / kSelectThreads), block, 0,
+                       stream, sa.hist, n_zero);
+    hipLaunchKernelGGL(select_split_kernel<0>, split_grid, block, 0, stream, sa);
+    hipLaunchKernelGGL(select_split_kernel<1>, split_grid, block, 0, stream, sa);
+    hipLaunchKernelGGL(select_split_kernel<2>, split_grid, block, 0, stream, sa);
+    hipLaunchKernelGGL(select_split_kernel<3>, split_grid, block, 0, stream, sa);
+    hipLaunchKernelGGL(select_split_kernel<4>, split_grid, block, 0, stream, sa);
+  } else hipLaunchKernelGGL(select_kernel, grid, block, 0, stream, a);
   return hipGetLastError();
 }
 

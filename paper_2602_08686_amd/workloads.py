@@ -80,6 +80,17 @@ C5 = Workload("c5_bf16_gqa28x4_T64k_bz4", "bf16", 4, 28, 4, 128, 65536, 32, POOL
               seed=5, head_key_scale=True, gate=True)
 CONFIGS = (C1, C2, C3, C4, C5)
 
+# Length scaling at a fixed retained ratio (the paper's pressure-regime setting: budgets 256 / 512 / 1024 /
+# 2048 for 16k / 32k / 64k / 128k contexts) and the extreme 128-token budget at 32k, on C3's attention
+# shape. Batch 4 keeps one layer's K and V at 2 GiB for the longest context.
+def _sweep(name: str, seq_len: int, budget: int, seed: int) -> Workload:
+    return C3.scaled(name=name, batch=4, seq_len=seq_len, budget=budget, seed=seed)
+
+
+SWEEP = (_sweep("s16k_b256_gqa32x8_bz4", 16384, 256, 11), _sweep("s32k_b512_gqa32x8_bz4", 32768, 512, 12),
+         _sweep("s64k_b1024_gqa32x8_bz4", 65536, 1024, 13), _sweep("s128k_b2048_gqa32x8_bz4", 131072, 2048, 14),
+         _sweep("s32k_b128_gqa32x8_bz4", 32768, 128, 15))
+
 
 def _gen(device, *keys: int) -> torch.Generator:
     g = torch.Generator(device=device)

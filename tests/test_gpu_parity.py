@@ -222,15 +222,18 @@ def test_budget_rule_matches_oracle_on_skewed_shares():
         np.testing.assert_array_equal(bud.cpu().numpy()[0], oracle.budgets(Hkv, T, W, Bn, share[0]))
 
 
-def _select_case(u, tau, budget, W, cap):
+def _select_case(u, tau, budget, W, cap, with_workspace=False):
     Bz, Hkv, P = u.shape
     p = B.make_params(batch=Bz, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, seq_len=P + W, window=W,
                       dtype="bf16", pool=wl.POOL_NONE, pool_kernel=1, budget=W, cap=cap)
     idx = torch.full((Bz, Hkv, cap), -1, dtype=torch.int32, device=DEV)
     cnt = torch.zeros(Bz, Hkv, dtype=torch.int32, device=DEV)
     ut = torch.from_numpy(u).to(DEV) if u.size else torch.zeros(1, device=DEV)   # P = 0: never read
+    ws = None
+    if with_workspace:  # filled with ones: the selection must clear what it accumulates into
+        ws = torch.full((B.ckv_workspace_bytes(p),), 0x5A, dtype=torch.uint8, device=DEV)
     B.ckv_select_topk(p, ut, torch.from_numpy(budget).to(DEV),
-                      torch.from_numpy(tau).to(DEV), idx, cnt)
+                      torch.from_numpy(tau).to(DEV), idx, cnt, ws)
     torch.cuda.synchronize()
     oi, oc = oracle.select(u, tau, budget, W, cap)
     np.testing.assert_array_equal(cnt.cpu().numpy(), oc)
@@ -269,6 +272,29 @@ def test_select_long_context_unit():
     rng = np.random.default_rng(8)
     u = (rng.standard_normal((1, 2, 131072 - 64)) ** 2).astype(np.float32)
     _select_case(u, np.array([0.8], np.float32), np.array([[512, 700]], np.int32), 64, 1024)
+
+
+def test_select_split_over_workgroups_long_prefixes():
+    """Prefixes beyond 65536 positions with a workspace: several workgroups per unit, same unique result."""
+    rng = np.random.default_rng(9)
+    one, zero = np.ones(1, np.float32), np.zeros(1, np.float32)
+    u = (rng.standard_normal((1, 2, 131072 - 64)) ** 2).astype(np.float32)
+    _select_case(u, 0.8 * one, np.array([[512, 700]], np.int32), 64, 1024, True)
+    _select_case(u, zero, np.array([[2048, 16160]], np.int32), 32, 16160, True)
+    # ragged last slice, heavy ties, budgets from kp = 0 to beyond the cap
+    t = rng.choice(np.linspace(0, 2, 12).astype(np.float32), size=(2, 3, 70000))
+    _select_case(t, np.array([0.0, 0.9], np.float32), np.array([[16, 17, 600], [40000, 70016, 999999]], np.int32),
+                 16, 70016, True)
+    # all equal: every digit histogram has one bin; the position order decides
+    _select_case(np.full((1, 2, 65540), 0.75, np.float32), zero, np.array([[100, 65556]], np.int32), 16, 65556, True)
+    # elastic pool: fewer candidates than the budget, none, all
+    v = rng.random((4, 1, 90000)).astype(np.float32)
+    _select_case(v, np.array([0.9999, 2.0, 0.0, 0.5], np.float32), np.full((4, 1), 300, np.int32), 32, 300, True)
+    # values that differ only in the low mantissa bits, 25 slices
+    near = (np.float32(1.0) + np.arange(200000, dtype=np.float32) % 97 * np.float32(1.2e-7)).reshape(1, 1, -1)
+    _select_case(near.astype(np.float32), zero, np.array([[50032]], np.int32), 32, 50032, True)
+    # a prefix length that is not a multiple of four takes the streaming kernel, workspace or not
+    _select_case(rng.random((1, 1, 70001)).astype(np.float32), zero, np.array([[777]], np.int32), 32, 800, True)
 
 
 def test_gather_identity_and_determinism():
