@@ -282,3 +282,79 @@ def layer_shared_layer(alpha, k_bits, v_bits, v, *, W, B_layer, cap, w_head_row,
     idx, count = idx[:, 0], count[:, 0]
     return dict(rho=rho, utility=u, tau=tau_b, idx=idx, count=count,
                 k_out=gather_shared(k_bits, idx, count), v_out=gather_shared(v_bits, idx, count))
+
+
+# ---------------------------------------------------------------------------------------------------
+# Decode-side consumer (Proposition 1 and its proof in App. A): a decoding query attends over the
+# retained set only; the discarded mass m_t of its full attention row measures what compression lost.
+# Plain numpy in float64, rows written out explicitly.
+# ---------------------------------------------------------------------------------------------------
+def _logits(q_dec, keys, scale):
+    """q_dec [Bz,Hq,Nq,d], keys [Bz,Hkv,R,d] -> scaled logits [Bz,Hq,Nq,R] (query head h reads KV head h // G)."""
+    q = np.asarray(q_dec, dtype=np.float64)
+    k = np.asarray(keys, dtype=np.float64)
+    G = q.shape[1] // k.shape[1]
+    s = (1.0 / np.sqrt(q.shape[-1])) if scale is None else float(scale)
+    return s * np.einsum("bhqd,bhrd->bhqr", q, np.repeat(k, G, axis=1))
+
+
+def decode_attention(q_dec, keys, values, count=None, scale=None):
+    """Attention of decoding queries (positions after the prompt: every row is visible) over a ragged KV
+    set: keys/values [Bz,Hkv,R,d] of which the first count[b,g] rows are valid (all R if count is None).
+    Returns (out [Bz,Hq,Nq,d], lse [Bz,Hq,Nq]) with lse = log sum_j exp z_j over the valid rows -- the
+    compressed row of Proposition 1, p~ = p restricted to S and renormalised, applied to V."""
+    z = _logits(q_dec, keys, scale)
+    v = np.asarray(values, dtype=np.float64)
+    Bz, Hq, Nq, R = z.shape
+    G = Hq // v.shape[1]
+    out = np.zeros((Bz, Hq, Nq, v.shape[-1]))
+    lse = np.zeros((Bz, Hq, Nq))
+    for b in range(Bz):
+        for h in range(Hq):
+            n = R if count is None else int(count[b][h // G])
+            for i in range(Nq):
+                row = z[b, h, i, :n]
+                top = row.max()
+                e = np.exp(row - top)
+                lse[b, h, i] = top + np.log(e.sum())
+                out[b, h, i] = (e / e.sum()) @ v[b, h // G, :n]
+    return out, lse
+
+
+def attention_rows(q_dec, keys, idx=None, count=None, scale=None):
+    """Full attention rows p [Bz,Hq,Nq,T] of decoding queries over all T keys and, if idx/count
+    [Bz,Hkv,cap]/[Bz,Hkv] name a retained set S per KV head, the compressed rows p~ (zero outside S,
+    renormalised over S; Proposition 1)."""
+    z = _logits(q_dec, keys, scale)
+    p = np.exp(z - z.max(-1, keepdims=True))
+    p /= p.sum(-1, keepdims=True)
+    if idx is None:
+        return p
+    Bz, Hq, Nq, T = p.shape
+    G = Hq // np.asarray(keys).shape[1]
+    keep = np.zeros((Bz, Hq, 1, T), dtype=bool)
+    for b in range(Bz):
+        for h in range(Hq):
+            keep[b, h, 0, np.asarray(idx[b][h // G][: int(count[b][h // G])], dtype=np.int64)] = True
+    kept = np.where(keep, p, 0.0)
+    return p, kept / kept.sum(-1, keepdims=True)
+
+
+def discarded_mass(q_dec, keys, idx, count, scale=None):
+    """m [Bz,Hq,Nq]: the mass of each full attention row outside the retained set, summed term by term."""
+    p = attention_rows(q_dec, keys, scale=scale)
+    Bz, Hq, Nq, T = p.shape
+    G = Hq // np.asarray(keys).shape[1]
+    m = np.zeros((Bz, Hq, Nq))
+    for b in range(Bz):
+        for h in range(Hq):
+            out = np.ones(T, dtype=bool)
+            out[np.asarray(idx[b][h // G][: int(count[b][h // G])], dtype=np.int64)] = False
+            m[b, h] = p[b, h][:, out].sum(-1)
+    return m
+
+
+def tail_eps(mass):
+    """eps_tail [Bz,Hq] = sqrt(mean over the query rows of m^2) (Proposition 1)."""
+    m = np.asarray(mass, dtype=np.float64)
+    return np.sqrt((m * m).mean(-1))
