@@ -279,6 +279,42 @@ ckv_status ckv_shared_utility(const ckv_params *params, const float *alpha, cons
 ckv_status ckv_compact_kv_shared(const ckv_params *params, const void *k, const void *v, const int32_t *idx,
                                  const int32_t *count, void *k_out, void *v_out, void *hip_stream);
 
+/*
+ * Decode-side consumer of the compact cache (paper Sec. 4.5, Proposition 1; proof in App. A).
+ *
+ * ckv_decode_attention: attention of decoding queries over a ragged KV set. A decoding query sits after
+ * the prompt and sees every row. For batch element b, query head h (KV head g = h / G), query i < n_q:
+ *     z[j]   = softmax_scale * <q_dec[b,h,i,:], k_rows[b,g,j,:]>          j < n_valid(b,g)
+ *     lse    = log sum_j exp z[j]
+ *     out    = sum_j exp(z[j] - lse) * v_rows[b,g,j,:]
+ * with n_valid(b,g) = count[b,g] clamped to [0, n_rows] (n_rows if count is NULL). Over the compact
+ * cache written by ckv_compact_kv (strides {Hkv*cap*d, cap*d, d}, n_rows = cap, the call's count) this
+ * is the compressed row of Proposition 1, p~ = p restricted to the retained set and renormalised,
+ * applied to V; over the full cache (params' k_stride / v_stride, n_rows = T, count = NULL) it is the
+ * uncompressed attention and its lse is the full row's normaliser.
+ *
+ *   q_dec     in   [Bz,Hq,n_q,d] contiguous, params->dtype, 16-byte aligned
+ *   k_rows, v_rows in  rows of (batch, kv head) at element strides k_stride / v_stride over
+ *                  (batch, kv head, row); multiples of 16 bytes, row stride >= d; 16-byte aligned
+ *   count     in   [Bz,Hkv] int32 or NULL
+ *   out       out  [Bz,Hq,n_q,d] fp32 (zeros where no row is valid)
+ *   lse       out  [Bz,Hq,n_q] fp32, natural log (-inf where no row is valid)
+ *   workspace      ckv_decode_workspace_bytes(params, n_q, n_rows) bytes, 256-byte aligned; that
+ *                  function returns 0 for arguments this call rejects
+ *
+ * ckv_discarded_mass: m[b,h,i] = 1 - exp(lse_kept - lse_full), the mass the full attention row had
+ * outside the retained set (Proposition 1; the row's l1 error is exactly 2m), clamped to [0,1], and
+ * eps_tail[b,h] = sqrt(mean_i m^2) (may be NULL).
+ *   lse_full, lse_kept  in  [Bz,Hq,n_q] fp32     mass out [Bz,Hq,n_q] fp32     eps_tail out [Bz,Hq] fp32
+ */
+size_t ckv_decode_workspace_bytes(const ckv_params *params, int32_t n_q, int32_t n_rows);
+ckv_status ckv_decode_attention(const ckv_params *params, const void *q_dec, int32_t n_q, const void *k_rows,
+                                const void *v_rows, const int64_t *k_stride, const int64_t *v_stride,
+                                int32_t n_rows, const int32_t *count, float *out, float *lse, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+ckv_status ckv_discarded_mass(const ckv_params *params, int32_t n_q, const float *lse_full, const float *lse_kept,
+                              float *mass, float *eps_tail, void *hip_stream);
+
 const char *ckv_status_string(ckv_status status);
 
 #ifdef __cplusplus

@@ -23,7 +23,7 @@ FLAG_SCAN_SINGLE_READ = 4   # force the persistent scan that reads K once (where
 
 EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_alpha_accumulate", "ckv_risk_struct", "ckv_shared_utility", "ckv_compact_kv_shared",
-           "ckv_status_string")
+           "ckv_decode_workspace_bytes", "ckv_decode_attention", "ckv_discarded_mass", "ckv_status_string")
 
 
 class CkvParams(ctypes.Structure):
@@ -81,6 +81,13 @@ def load(path: Optional[Path] = None):
     lib.ckv_shared_utility.restype = ctypes.c_int
     lib.ckv_compact_kv_shared.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
     lib.ckv_compact_kv_shared.restype = ctypes.c_int
+    lib.ckv_decode_workspace_bytes.argtypes = [pp, ctypes.c_int32, ctypes.c_int32]
+    lib.ckv_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.ckv_decode_attention.argtypes = [pp, vp, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, vp,
+                                         ctypes.c_size_t, vp]
+    lib.ckv_decode_attention.restype = ctypes.c_int
+    lib.ckv_discarded_mass.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp]
+    lib.ckv_discarded_mass.restype = ctypes.c_int
     lib.ckv_status_string.argtypes = [ctypes.c_int]
     lib.ckv_status_string.restype = ctypes.c_char_p
     if path is None:
@@ -213,6 +220,28 @@ def ckv_shared_utility(params, alpha, vnorm_ratio, w_head, t_gate, n_ent, n_ppl,
 def ckv_compact_kv_shared(params, k, v, idx, count, k_out, v_out, stream=None):
     _check(load().ckv_compact_kv_shared(ctypes.byref(params), _ptr(k), _ptr(v), _ptr(idx), _ptr(count),
                                         _ptr(k_out), _ptr(v_out), _stream(stream)), "ckv_compact_kv_shared")
+
+
+def ckv_decode_workspace_bytes(params, n_q, n_rows) -> int:
+    return int(load().ckv_decode_workspace_bytes(ctypes.byref(params), int(n_q), int(n_rows)))
+
+
+def ckv_decode_attention(params, q_dec, k_rows, v_rows, count, out, lse, workspace, stream=None):
+    """q_dec [Bz,Hq,n_q,d]; k_rows / v_rows [Bz,Hkv,n_rows,d] (any strides over the first three axes);
+    count [Bz,Hkv] int32 or None."""
+    n_q, n_rows = q_dec.shape[2], k_rows.shape[2]
+    ks = (ctypes.c_int64 * 3)(*k_rows.stride()[:3])
+    vs = (ctypes.c_int64 * 3)(*v_rows.stride()[:3])
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().ckv_decode_attention(ctypes.byref(params), _ptr(q_dec), int(n_q), _ptr(k_rows), _ptr(v_rows),
+                                       ctypes.cast(ks, ctypes.c_void_p), ctypes.cast(vs, ctypes.c_void_p),
+                                       int(n_rows), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes,
+                                       _stream(stream)), "ckv_decode_attention")
+
+
+def ckv_discarded_mass(params, n_q, lse_full, lse_kept, mass, eps_tail=None, stream=None):
+    _check(load().ckv_discarded_mass(ctypes.byref(params), int(n_q), _ptr(lse_full), _ptr(lse_kept), _ptr(mass),
+                                     _ptr(eps_tail), _stream(stream)), "ckv_discarded_mass")
 
 
 class LayerBuffers:

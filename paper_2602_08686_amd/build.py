@@ -11,7 +11,7 @@ CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB = PKG / "libckv.so"
 SCAN_SOURCES = ["ckv_scan_bf16_d128.hip", "ckv_scan_bf16_d64.hip", "ckv_scan_f32_d64.hip", "ckv_scan_f32_d128.hip"]
-SOURCES = SCAN_SOURCES + ["ckv_api.hip", "ckv_scores.hip", "ckv_tables.hip", "ckv_select.hip", "ckv_gather.hip", "ckv_shared.hip"]
+SOURCES = SCAN_SOURCES + ["ckv_api.hip", "ckv_scores.hip", "ckv_tables.hip", "ckv_select.hip", "ckv_gather.hip", "ckv_shared.hip", "ckv_decode.hip"]
 # Packed-FP32 instructions are switched off for the device pass (some forms have given wrong
 # results on the target machines); the host pass does not know the feature and says so, harmlessly.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

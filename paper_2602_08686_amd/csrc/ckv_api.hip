@@ -345,6 +345,60 @@ extern "C" ckv_status ckv_compact_kv_shared(const ckv_params *params, const void
   return CKV_OK;
 }
 
+static ckv_status decode_args_ok(const ckv_params *p, int32_t n_q, int32_t n_rows, const int64_t *k_stride,
+                                 const int64_t *v_stride) {
+  if (n_q < 1 || n_rows < 1 || !k_stride || !v_stride) return CKV_EINVAL;
+  const int64_t per16 = p->dtype == CKV_BF16 ? 8 : 4;
+  for (int i = 0; i < 3; ++i)
+    if (k_stride[i] < 0 || v_stride[i] < 0 || k_stride[i] % per16 || v_stride[i] % per16) return CKV_EINVAL;
+  if (k_stride[2] < p->head_dim || v_stride[2] < p->head_dim) return CKV_EINVAL;
+  if (n_rows > (1 << 24)) return CKV_EUNSUPPORTED;
+  return CKV_OK;
+}
+
+extern "C" size_t ckv_decode_workspace_bytes(const ckv_params *params, int32_t n_q, int32_t n_rows) {
+  if (validate(params) != CKV_OK || n_q < 1 || n_rows < 1) return 0;
+  Shape s;
+  derive(params, &s);
+  const DecodePlan plan = plan_decode(s, n_q, n_rows);
+  if (plan.grid_y > 65535) return 0;
+  return align256(plan.workspace_bytes);
+}
+
+extern "C" ckv_status ckv_decode_attention(const ckv_params *params, const void *q_dec, int32_t n_q,
+                                           const void *k_rows, const void *v_rows, const int64_t *k_stride,
+                                           const int64_t *v_stride, int32_t n_rows, const int32_t *count,
+                                           float *out, float *lse, void *workspace, size_t workspace_bytes,
+                                           void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!q_dec || !k_rows || !v_rows || !out || !lse) return CKV_EINVAL;
+  st = decode_args_ok(params, n_q, n_rows, k_stride, v_stride);
+  if (st != CKV_OK) return st;
+  if (((uintptr_t)q_dec | (uintptr_t)k_rows | (uintptr_t)v_rows) & 15) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  const DecodePlan plan = plan_decode(s, n_q, n_rows);
+  if (plan.grid_y > 65535) return CKV_EUNSUPPORTED;  // grid.y
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.workspace_bytes) return CKV_EWORKSPACE;
+  if (launch_decode_attention(params, s, q_dec, n_q, k_rows, v_rows, k_stride, v_stride, n_rows, count, out, lse,
+                              (char *)workspace, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+extern "C" ckv_status ckv_discarded_mass(const ckv_params *params, int32_t n_q, const float *lse_full,
+                                         const float *lse_kept, float *mass, float *eps_tail, void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (n_q < 1 || !lse_full || !lse_kept || !mass) return CKV_EINVAL;
+  Shape s;
+  derive(params, &s);
+  if (launch_discarded_mass(s, n_q, lse_full, lse_kept, mass, eps_tail, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
 extern "C" const char *ckv_status_string(ckv_status status) {
   switch (status) {
     case CKV_OK: return "ok";

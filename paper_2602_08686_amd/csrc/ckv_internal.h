@@ -102,5 +102,20 @@ hipError_t launch_shared_utility(const ckv_params *p, const Shape &s, const floa
                                  const float *w_head, const float *t_gate, int n_ent, int n_ppl,
                                  const int32_t *risk_bins, float *utility, float *tau, hipStream_t stream);
 
+// decode-side consumer (Proposition 1): attention over a ragged KV set, discarded mass
+struct DecodePlan {
+  int rq;              // query heads of a group that share one sweep over the rows (1, 2, 4 or 8)
+  int head_chunks;     // ceil(G / rq)
+  int rows_per_chunk, n_chunks;
+  int64_t grid_y;      // Bz * Hkv * n_q * head_chunks
+  size_t workspace_bytes;
+};
+DecodePlan plan_decode(const Shape &s, int n_q, int n_rows);
+hipError_t launch_decode_attention(const ckv_params *p, const Shape &s, const void *q_dec, int n_q, const void *k_rows,
+                                   const void *v_rows, const int64_t *k_stride, const int64_t *v_stride, int n_rows,
+                                   const int32_t *count, float *out, float *lse, char *ws, hipStream_t stream);
+hipError_t launch_discarded_mass(const Shape &s, int n_q, const float *lse_full, const float *lse_kept, float *mass,
+                                 float *eps, hipStream_t stream);
+
 }  // namespace ckv
 #endif

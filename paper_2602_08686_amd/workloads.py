@@ -162,3 +162,11 @@ def make_layer(w: Workload, layer: int = 0, device="cpu") -> dict:
                     j = int(torch.randint(0, W, (1,), generator=gc))
                     k[b, kv, pos[n]] = (4.0 * q[b, h, j].to(torch.float32)).to(dt)
     return {"q": q, "k": k, "v": v, "needle_pos": needle_pos}
+
+
+def make_decode_queries(w: Workload, layer: int, n_q: int, device="cpu") -> torch.Tensor:
+    """Queries of n_q decoding steps after the prompt, [Bz,Hq,n_q,d] in the workload's dtype: drawn like
+    the window's query rows (the decoding queries of a real model continue the prompt's last rows)."""
+    g = _gen(device, w.seed, layer, 2)
+    q = torch.randn(w.batch, w.n_q_heads, n_q, w.head_dim, generator=g, device=device, dtype=torch.float32)
+    return q.to(w.torch_dtype)
