@@ -157,6 +157,113 @@ def layer_shared_bench(args, w, n_layers, torch, B, wl) -> int:
     return 0
 
 
+def decode_bench(args, w, n_layers, torch, B, wl) -> int:
+    """Decode-side consumer: a step = one decoding query per head attending over the compact cache of every
+    layer. The same call over the full cache and the discarded-mass kernel are timed beside it."""
+    dev = "cuda"
+    tables = wl.make_tables(w, dev)
+    e = 2 if w.dtype == "bf16" else 4
+    caches, full = [], []
+    for l in range(n_layers):
+        t = wl.make_layer(w, l % w.n_layers, dev)
+        p = B.params_for(t["q"], t["k"], t["v"], pool=w.pool, pool_kernel=w.pool_kernel, budget=w.budget, cap=w.cap,
+                         layer=l % w.n_layers, n_layers=w.n_layers)
+        buf = B.LayerBuffers(p, dev)
+        B.retention_layer(p, t["q"], t["k"], t["v"], tables, buf, fused_utility=True)
+        torch.cuda.synchronize()
+        caches.append((p, buf.k_out, buf.v_out, buf.count, wl.make_decode_queries(w, l % w.n_layers, 1, dev)))
+        if l < 4:
+            full.append((t["k"], t["v"]))
+        del buf.scores, t
+    kept = sum(int(c[3].sum().item()) for c in caches) / n_layers
+    out = torch.empty(w.batch, w.n_q_heads, 1, w.head_dim, device=dev)
+    lse_c, lse_f = torch.empty(w.batch, w.n_q_heads, 1, device=dev), torch.empty(w.batch, w.n_q_heads, 1, device=dev)
+    mass, eps = torch.empty(w.batch, w.n_q_heads, 1, device=dev), torch.empty(w.batch, w.n_q_heads, device=dev)
+    p0 = caches[0][0]
+    ws = torch.empty(max(B.ckv_decode_workspace_bytes(p0, 1, w.seq_len), B.ckv_decode_workspace_bytes(p0, 1, w.cap)),
+                     dtype=torch.uint8, device=dev)
+
+    def step():
+        for p, kc, vc, cnt, qd in caches:
+            B.ckv_decode_attention(p, qd, kc, vc, cnt, out, lse_c, ws)
+
+    # A decoding step is tens of short launches: queued one by one the host's launch cost bounds it, so the
+    # step is captured once into a HIP graph and replayed (no memset nodes: the calls only launch kernels).
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    eager_out, eager_lse = out.clone(), lse_c.clone()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_eager = (time.perf_counter() - t0) * 1e3 / args.steps
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(max(args.warmup, 1)):
+        graph.replay()
+        torch.cuda.synchronize()
+        if not (torch.equal(out, eager_out) and torch.equal(lse_c, eager_lse)):
+            print("bench.py: graph replay differs from the eager result", file=sys.stderr)
+            return 4
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    if not (torch.equal(out, eager_out) and torch.equal(lse_c, eager_lse)):
+        print("bench.py: graph replay differs from the eager result", file=sys.stderr)
+        return 4
+    ms_per_layer = ms_per_step / n_layers
+    q_out_bytes = w.batch * w.n_q_heads * w.head_dim * (e + 4)
+    compact_bytes = 2 * kept * w.head_dim * e + q_out_bytes          # every retained K and V row once
+    full_bytes = 2 * w.batch * w.n_kv_heads * w.seq_len * w.head_dim * e + q_out_bytes
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    pairs_f, pairs_m = [], []
+    for i in range(max(8, 2 * args.steps)):
+        k, v = full[i % len(full)]
+        p, kc, vc, cnt, qd = caches[i % len(full)]
+        a, b_, c = ev(), ev(), ev()
+        a.record()
+        B.ckv_decode_attention(p, qd, k, v, None, out, lse_f, ws)
+        b_.record()
+        B.ckv_discarded_mass(p, 1, lse_f, lse_c, mass, eps)
+        c.record()
+        pairs_f.append((a, b_))
+        pairs_m.append((b_, c))
+    torch.cuda.synchronize()
+    ms_full = sorted(a.elapsed_time(b_) for a, b_ in pairs_f)[len(pairs_f) // 2]
+    ms_mass = sorted(a.elapsed_time(b_) for a, b_ in pairs_m)[len(pairs_m) // 2]
+    # discarded mass of the last layer timed, from its own two normalisers
+    p, kc, vc, cnt, qd = caches[0]
+    B.ckv_decode_attention(p, qd, kc, vc, cnt, out, lse_c, ws)
+    B.ckv_decode_attention(p, qd, full[0][0], full[0][1], None, out, lse_f, ws)
+    B.ckv_discarded_mass(p, 1, lse_f, lse_c, mass, eps)
+    torch.cuda.synchronize()
+    value = compact_bytes / (ms_per_layer * 1e-3) / 1e9
+    full_gbs = full_bytes / (ms_full * 1e-3) / 1e9
+    line = {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) of one decoding step's attention over the compact cache",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_layer": round(ms_per_layer, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "mode": "decode (consumer of the compact cache)", "layers_per_step": n_layers,
+                   "batch": w.batch, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "seq_len": w.seq_len, "budget_per_kv_head": w.budget, "kept_rows_per_layer": kept,
+                   "algorithmic_bytes_per_layer": int(compact_bytes), "launch": "HIP graph replay",
+                   "ms_per_step_eager_launches": round(ms_eager, 4)},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel (full cache)", "achieved": round(full_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(full_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "ms_per_launch": round(ms_full, 4), "discarded_mass_ms": round(ms_mass, 4),
+                     "compact_cache_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+        "discarded_mass": {"mean": round(float(mass.mean().item()), 6), "max": round(float(mass.max().item()), 6),
+                           "mean_eps_tail": round(float(eps.mean().item()), 6), "layer": 0},
+    }
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,9 +281,10 @@ def main() -> int:
     ap.add_argument("--unfused", action="store_true",
                     help="ckv_window_scores + ckv_apply_tables instead of ckv_window_utility (materialises the "
                          "per-head window mass)")
-    ap.add_argument("--mode", default="per_head", choices=["per_head", "layer_shared"],
+    ap.add_argument("--mode", default="per_head", choices=["per_head", "layer_shared", "decode"],
                     help="per_head: the north-star path (default). layer_shared: the paper's Alg. 1 as printed, one "
-                         "alpha per prompt and one index set per layer (reported with the same metric)")
+                         "alpha per prompt and one index set per layer (reported with the same metric). decode: the "
+                         "decode-side consumer, one decoding query per head over every layer's compact cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=0, help="batch elements in the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -205,6 +313,8 @@ def main() -> int:
 
     if args.mode == "layer_shared":
         return layer_shared_bench(args, w, n_layers, torch, B, wl)
+    if args.mode == "decode":
+        return decode_bench(args, w, n_layers, torch, B, wl)
     tables = wl.make_tables(w, dev)
     layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
     q0, k0, v0 = layers[0]["q"], layers[0]["k"], layers[0]["v"]

@@ -299,8 +299,10 @@ ckv_status ckv_compact_kv_shared(const ckv_params *params, const void *k, const 
  *   count     in   [Bz,Hkv] int32 or NULL
  *   out       out  [Bz,Hq,n_q,d] fp32 (zeros where no row is valid)
  *   lse       out  [Bz,Hq,n_q] fp32, natural log (-inf where no row is valid)
- *   workspace      ckv_decode_workspace_bytes(params, n_q, n_rows) bytes, 256-byte aligned; that
- *                  function returns 0 for arguments this call rejects
+ *   workspace      ckv_decode_workspace_bytes(params, n_q, n_rows) bytes, 256-byte aligned. That
+ *                  function returns 0 for arguments this call rejects, and also for short KV sets
+ *                  (n_rows <= 4096), which one launch finishes without scratch: workspace may then
+ *                  be NULL.
  *
  * ckv_discarded_mass: m[b,h,i] = 1 - exp(lse_kept - lse_full), the mass the full attention row had
  * outside the retained set (Proposition 1; the row's l1 error is exactly 2m), clamped to [0,1], and

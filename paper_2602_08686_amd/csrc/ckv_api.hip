@@ -380,7 +380,9 @@ extern "C" ckv_status ckv_decode_attention(const ckv_params *params, const void 
   derive(params, &s);
   const DecodePlan plan = plan_decode(s, n_q, n_rows);
   if (plan.grid_y > 65535) return CKV_EUNSUPPORTED;  // grid.y
-  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.workspace_bytes) return CKV_EWORKSPACE;
+  if (plan.workspace_bytes > 0 &&
+      (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.workspace_bytes))
+    return CKV_EWORKSPACE;
   if (launch_decode_attention(params, s, q_dec, n_q, k_rows, v_rows, k_stride, v_stride, n_rows, count, out, lse,
                               (char *)workspace, (hipStream_t)hip_stream) != hipSuccess)
     return CKV_EHIP;

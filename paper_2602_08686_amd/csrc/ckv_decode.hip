@@ -30,7 +30,6 @@ struct DecodeArgs {
 
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / kWave;
-constexpr int kDecodeSteps = 4;  // row steps whose loads are in flight together
 
 template <int DT>
 struct Piece;  // a 16-byte piece of a row as floats
@@ -57,18 +56,51 @@ struct Piece<CKV_F32> {
   }
 };
 
+// Sum over the LPR (8, 16 or 32) consecutive lanes that hold one row; every lane ends with the total.
+// Lane exchanges inside a row of 16 lanes are DPP operands of the add (quad permutes give the xor-1 and
+// xor-2 partners; once quads agree, mirroring a half row or a row pairs each lane with its xor-4 /
+// xor-8 partner's value); only 32-lane rows need one exchange through the LDS crossbar.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_d;
+// A 16-byte piece of a row; STREAM marks data that is used once (non-temporal: it should not displace
+// what the caches hold).
+template <bool STREAM>
+__device__ __forceinline__ uint4 load_piece(const char *p) {
+  if (STREAM) {
+    const u32x4_d v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_d *>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+  }
+  return *reinterpret_cast<const uint4 *>(p);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false);
+  return x + __int_as_float(y);
+}
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+  x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);                 // row_half_mirror
+  if (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror
+  if (LPR >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
 // exp2(a - b) with the conventions of an online softmax: a = -inf gives 0 also when b was reset to 0
 __device__ __forceinline__ float exp2_diff(float a, float b) { return exp2f(a - b); }
 
-template <int DT, int DH, int RQ>
-__global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeArgs a) {
+// NW waves per workgroup, U row steps whose loads are in flight together. With one chunk per
+// (unit, query) the workgroup writes the final result itself and no merge kernel follows.
+template <int DT, int DH, int RQ, int NW, int U>
+__global__ void __launch_bounds__(NW *kWave) decode_partial_kernel(DecodeArgs a) {
   constexpr int E = Piece<DT>::E;
   constexpr int ESIZE = 16 / E;
   constexpr int LPR = DH / E;        // lanes per row
   constexpr int KPW = kWave / LPR;   // rows per wave step
-  constexpr int U = kDecodeSteps;
   constexpr int ROW = DH + 2;
-  __shared__ float sm[kDecodeWaves][RQ][ROW];
+  constexpr bool STREAM = NW == kDecodeWaves;  // the chunked form sweeps long caches once: streaming loads
+  __shared__ float sm[NW][RQ][ROW];
 
   const int chunk = blockIdx.x;
   int y = blockIdx.y;
@@ -81,6 +113,8 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeAr
   int n_valid = a.n_rows;
   if (a.count) n_valid = min(max(a.count[unit], 0), a.n_rows);
   const int r0 = chunk * a.rows_per_chunk, r1 = min(r0 + a.rows_per_chunk, n_valid);
+  const bool single = a.n_chunks == 1;
+  if (r0 >= r1 && !single) return;  // the merge reads the chunks below n_valid only
 
   float qv[RQ][E];
 #pragma unroll
@@ -108,7 +142,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeAr
   const char *kb = static_cast<const char *>(a.k) + ((size_t)b * a.ks[0] + (size_t)g * a.ks[1]) * ESIZE;
   const char *vb = static_cast<const char *>(a.v) + ((size_t)b * a.vs[0] + (size_t)g * a.vs[1]) * ESIZE;
   // a wave takes KPW * U consecutive rows at a time; the workgroup's waves interleave such blocks
-  for (int base = r0 + wave * KPW * U; base < r1; base += kDecodeWaves * KPW * U) {
+  for (int base = r0 + wave * KPW * U; base < r1; base += NW * KPW * U) {
     uint4 kraw[U], vraw[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -116,8 +150,8 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeAr
       kraw[u] = make_uint4(0u, 0u, 0u, 0u);
       vraw[u] = make_uint4(0u, 0u, 0u, 0u);
       if (row < r1) {
-        kraw[u] = *reinterpret_cast<const uint4 *>(kb + ((size_t)row * a.ks[2] + sub * E) * ESIZE);
-        vraw[u] = *reinterpret_cast<const uint4 *>(vb + ((size_t)row * a.vs[2] + sub * E) * ESIZE);
+        kraw[u] = load_piece<STREAM>(kb + ((size_t)row * a.ks[2] + sub * E) * ESIZE);
+        vraw[u] = load_piece<STREAM>(vb + ((size_t)row * a.vs[2] + sub * E) * ESIZE);
       }
     }
     float s[U][RQ], vf[U][E];
@@ -132,8 +166,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeAr
         float dot = 0.0f;
 #pragma unroll
         for (int e = 0; e < E; ++e) dot = fmaf(qv[r][e], kf[e], dot);
-#pragma unroll
-        for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);  // the row's lanes all end with the sum
+        dot = row_sum<LPR>(dot);  // the row's lanes all end with the sum
         s[u][r] = ok ? dot : -INFINITY;
       }
     }
@@ -191,12 +224,34 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeAr
     }
   }
   __syncthreads();
+  if (single) {
+    for (int i = tid; i < RQ * DH; i += NW * kWave) {
+      const int r = i / DH, c = i % DH;
+      const int hg = hc * RQ + r;
+      if (hg >= a.G) continue;
+      float top = sm[0][r][DH];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) top = fmaxf(top, sm[w][r][DH]);
+      const float ref = top == -INFINITY ? 0.0f : top;
+      float num = 0.0f, den = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const float f = exp2_diff(sm[w][r][DH], ref);
+        num = fmaf(sm[w][r][c], f, num);
+        den = fmaf(sm[w][r][DH + 1], f, den);
+      }
+      const size_t row = ((size_t)b * a.Hq + (size_t)g * a.G + hg) * a.n_q + qi;
+      a.out[row * DH + c] = den > 0.0f ? num / den : 0.0f;
+      if (c == 0) a.lse[row] = den > 0.0f ? (top + log2f(den)) * kLn2 : -INFINITY;
+    }
+    return;
+  }
   float *part = a.part + ((size_t)blockIdx.y * a.n_chunks + chunk) * RQ * ROW;
-  for (int i = tid; i < RQ * ROW; i += kDecodeThreads) {
+  for (int i = tid; i < RQ * ROW; i += NW * kWave) {
     const int r = i / ROW, c = i % ROW;
     float top = sm[0][r][DH];
 #pragma unroll
-    for (int w = 1; w < kDecodeWaves; ++w) top = fmaxf(top, sm[w][r][DH]);
+    for (int w = 1; w < NW; ++w) top = fmaxf(top, sm[w][r][DH]);
     const float ref = top == -INFINITY ? 0.0f : top;
     float val;
     if (c == DH) val = top;
@@ -204,11 +259,13 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_partial_kernel(DecodeAr
       const int src = c < DH ? c : DH + 1;  // a V component, or the sum
       val = 0.0f;
 #pragma unroll
-      for (int w = 0; w < kDecodeWaves; ++w) val = fmaf(sm[w][r][src], exp2_diff(sm[w][r][DH], ref), val);
+      for (int w = 0; w < NW; ++w) val = fmaf(sm[w][r][src], exp2_diff(sm[w][r][DH], ref), val);
     }
     part[i] = val;
   }
 }
+
+constexpr int kMergeBatch = 16;  // chunks whose partials are loaded together
 
 template <int DH, int RQ>
 __global__ void __launch_bounds__(kDecodeThreads) decode_merge_kernel(DecodeArgs a) {
@@ -218,20 +275,41 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_merge_kernel(DecodeArgs
   y /= a.head_chunks;
   const int qi = y % a.n_q, unit = y / a.n_q;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
+  int n_valid = a.n_rows;
+  if (a.count) n_valid = min(max(a.count[unit], 0), a.n_rows);
+  const int n_chunks = (n_valid + a.rows_per_chunk - 1) / a.rows_per_chunk;  // the chunks that were written
   const float *part = a.part + (size_t)blockIdx.x * a.n_chunks * RQ * ROW;
   for (int i = threadIdx.x; i < RQ * DH; i += kDecodeThreads) {
     const int r = i / DH, c = i % DH;
     const int hg = hc * RQ + r;
     if (hg >= a.G) continue;
-    float top = -INFINITY;
-    for (int ch = 0; ch < a.n_chunks; ++ch) top = fmaxf(top, part[((size_t)ch * RQ + r) * ROW + DH]);
-    const float ref = top == -INFINITY ? 0.0f : top;
-    float num = 0.0f, den = 0.0f;
-    for (int ch = 0; ch < a.n_chunks; ++ch) {
-      const float *p = part + ((size_t)ch * RQ + r) * ROW;
-      const float f = exp2_diff(p[DH], ref);
-      num = fmaf(p[c], f, num);
-      den = fmaf(p[DH + 1], f, den);
+    // online merge in chunk order, a batch of independent loads at a time
+    float top = -INFINITY, num = 0.0f, den = 0.0f;
+    for (int c0 = 0; c0 < n_chunks; c0 += kMergeBatch) {
+      float pm[kMergeBatch], pl[kMergeBatch], pa[kMergeBatch];
+#pragma unroll
+      for (int j = 0; j < kMergeBatch; ++j) {
+        const bool ok = c0 + j < n_chunks;
+        const float *p = part + ((size_t)(ok ? c0 + j : 0) * RQ + r) * ROW;
+        pm[j] = ok ? p[DH] : -INFINITY;
+        pl[j] = ok ? p[DH + 1] : 0.0f;
+        pa[j] = ok ? p[c] : 0.0f;
+      }
+      float mx = pm[0];
+#pragma unroll
+      for (int j = 1; j < kMergeBatch; ++j) mx = fmaxf(mx, pm[j]);
+      const float m_new = fmaxf(top, mx);
+      const float ref = m_new == -INFINITY ? 0.0f : m_new;
+      const float keep = exp2_diff(top, ref);
+      num *= keep;
+      den *= keep;
+#pragma unroll
+      for (int j = 0; j < kMergeBatch; ++j) {
+        const float f = exp2_diff(pm[j], ref);
+        num = fmaf(pa[j], f, num);
+        den = fmaf(pl[j], f, den);
+      }
+      top = m_new;
     }
     const size_t row = ((size_t)b * a.Hq + (size_t)g * a.G + hg) * a.n_q + qi;
     a.out[row * DH + c] = den > 0.0f ? num / den : 0.0f;
@@ -249,9 +327,23 @@ DecodePlan plan_decode(const Shape &s, int n_q, int n_rows) {
   p.rq = query_rows_per_pass(s.G);
   p.head_chunks = (s.G + p.rq - 1) / p.rq;
   p.grid_y = (int64_t)s.Bz * s.Hkv * n_q * p.head_chunks;
-  // enough workgroups to fill the chip, chunks of at least 256 rows, at most 64 chunks
-  const int64_t want = (2048 + p.grid_y - 1) / p.grid_y;
-  int64_t chunks = (n_rows + 255) / 256;
+  // Short KV sets (a compact cache): one large workgroup per (unit, query, pair of heads) finishes the job
+  // in one launch -- a decoding step is a chain of dependent layers, so a second launch costs more than
+  // reading the few rows once per pair of heads (the second read hits the cache), and two heads per
+  // workgroup leave registers for sixteen waves with four row steps in flight each.
+  if (n_rows <= 4096 || (p.grid_y >= 1024 && n_rows <= 16384)) {
+    p.rq = s.G >= 2 ? 2 : 1;
+    p.head_chunks = (s.G + p.rq - 1) / p.rq;
+    p.grid_y = (int64_t)s.Bz * s.Hkv * n_q * p.head_chunks;
+    p.rows_per_chunk = (n_rows + 63) / 64 * 64;
+    p.n_chunks = 1;
+    p.workspace_bytes = 0;
+    return p;
+  }
+  // enough workgroups to fill the chip several times, chunks of at least 64 rows (one step of a
+  // workgroup's four waves), at most 64 chunks
+  const int64_t want = (4096 + p.grid_y - 1) / p.grid_y;
+  int64_t chunks = (n_rows + 63) / 64;
   if (chunks > want) chunks = want;
   if (chunks > 64) chunks = 64;
   if (chunks < 1) chunks = 1;
@@ -265,8 +357,14 @@ DecodePlan plan_decode(const Shape &s, int n_q, int n_rows) {
 
 template <int DT, int DH, int RQ>
 static void launch_decode_t(const DecodeArgs &a, const DecodePlan &p, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ>), dim3(p.n_chunks, (unsigned)p.grid_y), dim3(kDecodeThreads),
-                     0, stream, a);
+  if (p.n_chunks == 1) {
+    if constexpr (RQ <= 2)
+      hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ, 16, 4>), dim3(1, (unsigned)p.grid_y), dim3(16 * kWave), 0,
+                         stream, a);
+    return;
+  }
+  hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ, kDecodeWaves, 4>), dim3(p.n_chunks, (unsigned)p.grid_y),
+                     dim3(kDecodeThreads), 0, stream, a);
   hipLaunchKernelGGL((decode_merge_kernel<DH, RQ>), dim3((unsigned)p.grid_y), dim3(kDecodeThreads), 0, stream, a);
 }
 

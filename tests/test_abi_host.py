@@ -164,27 +164,29 @@ def test_decode_consumer_entry_points_are_validated_on_the_host():
     p = _good()
     ref = ctypes.byref
     d = ctypes.c_void_p(256)
-    need = B.ckv_decode_workspace_bytes(p, 1, 544)
+    rows = 20000
+    need = B.ckv_decode_workspace_bytes(p, 1, rows)
     assert need > 0 and need % 256 == 0
-    assert B.ckv_decode_workspace_bytes(p, 0, 544) == 0 and B.ckv_decode_workspace_bytes(p, 1, 0) == 0
-    assert B.ckv_decode_workspace_bytes(p, 4, p.seq_len) >= need
-    good = (ctypes.c_int64 * 3)(8 * 544 * 128, 544 * 128, 128)
+    assert B.ckv_decode_workspace_bytes(p, 0, rows) == 0 and B.ckv_decode_workspace_bytes(p, 1, 0) == 0
+    assert B.ckv_decode_workspace_bytes(p, 4, rows) >= need
+    assert B.ckv_decode_workspace_bytes(p, 1, 544) == 0          # a short KV set is finished by one launch: no scratch
+    good = (ctypes.c_int64 * 3)(8 * rows * 128, rows * 128, 128)
     st = lambda a: ctypes.cast(a, ctypes.c_void_p)
     da = lambda **kw: lib.ckv_decode_attention(
         ref(p), kw.get("q", d), kw.get("n_q", 1), kw.get("k", d), kw.get("v", d), st(kw.get("ks", good)),
-        st(kw.get("vs", good)), kw.get("n_rows", 544), kw.get("count"), kw.get("out", d), kw.get("lse", d),
+        st(kw.get("vs", good)), kw.get("n_rows", rows), kw.get("count"), kw.get("out", d), kw.get("lse", d),
         kw.get("ws", d), kw.get("ws_bytes", need), None)
     for name in ("q", "k", "v", "out", "lse"):
         assert da(**{name: None}) == B.CKV_EINVAL
     assert da(q=ctypes.c_void_p(264)) == B.CKV_EINVAL                               # 16-byte alignment
     assert da(n_q=0) == B.CKV_EINVAL and da(n_rows=0) == B.CKV_EINVAL
-    assert da(ks=(ctypes.c_int64 * 3)(8 * 544 * 128, 544 * 128, 64)) == B.CKV_EINVAL    # rows overlap
-    assert da(vs=(ctypes.c_int64 * 3)(8 * 544 * 128, 544 * 128 + 4, 128)) == B.CKV_EINVAL  # not 16-byte pieces
-    assert da(ks=(ctypes.c_int64 * 3)(-1, 544 * 128, 128)) == B.CKV_EINVAL
+    assert da(ks=(ctypes.c_int64 * 3)(8 * rows * 128, rows * 128, 64)) == B.CKV_EINVAL    # rows overlap
+    assert da(vs=(ctypes.c_int64 * 3)(8 * rows * 128, rows * 128 + 4, 128)) == B.CKV_EINVAL  # not 16-byte pieces
+    assert da(ks=(ctypes.c_int64 * 3)(-1, rows * 128, 128)) == B.CKV_EINVAL
     assert da(ws=None) == B.CKV_EWORKSPACE and da(ws_bytes=need - 256) == B.CKV_EWORKSPACE
     assert da(ws=ctypes.c_void_p(272)) == B.CKV_EWORKSPACE
     assert da(n_q=20000) == B.CKV_EUNSUPPORTED                                       # more query rows than one launch takes
-    assert B.ckv_decode_workspace_bytes(p, 20000, 544) == 0
+    assert B.ckv_decode_workspace_bytes(p, 20000, rows) == 0
     dm = lambda **kw: lib.ckv_discarded_mass(ref(p), kw.get("n_q", 1), kw.get("lf", d), kw.get("lk", d),
                                              kw.get("mass", d), None, None)
     for name in ("lf", "lk", "mass"):

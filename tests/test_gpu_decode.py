@@ -28,7 +28,7 @@ CASES = [
     (_w("dec_bf16_gqa7", "bf16", 1, 7, 1, 128, 2500, 32, 300), 2),         # eight rows per sweep, one padded
     (_w("dec_bf16_gqa3_d64", "bf16", 2, 6, 2, 64, 1111, 16, 77), 1),       # three heads pad to four; 128-byte rows
     (_w("dec_bf16_gqa16", "bf16", 1, 16, 1, 128, 900, 32, 64), 1),         # two sweeps of eight heads
-    (_w("dec_bf16_gqa2", "bf16", 1, 4, 2, 128, 70000, 64, 1000), 2),       # many chunks
+    (_w("dec_bf16_gqa2", "bf16", 1, 4, 2, 128, 70000, 64, 6000), 2),       # many chunks, also over the compact cache
     (_w("dec_f32_mha", "f32", 1, 4, 4, 64, 1024, 32, 128), 2),
     (_w("dec_f32_gqa2_d128", "f32", 2, 4, 2, 128, 777, 20, 60), 1),
 ]
