@@ -35,6 +35,37 @@ struct Shape {
   bool fused;       // ... and is the one ckv_window_scores uses when it computes LSE itself
 };
 
+// A 16-byte piece of a row; STREAM marks data that is used once (non-temporal: it should not displace
+// what the caches hold).
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_d;
+template <bool STREAM>
+__device__ __forceinline__ uint4 load_piece(const char *p) {
+  if (STREAM) {
+    const u32x4_d v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_d *>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+  }
+  return *reinterpret_cast<const uint4 *>(p);
+}
+
+// Sum over the LPR (8, 16 or 32) consecutive lanes that hold one row; every lane ends with the total.
+// Lane exchanges inside a row of 16 lanes are DPP operands of the add (quad permutes give the xor-1 and
+// xor-2 partners; once quads agree, mirroring a half row or a row pairs each lane with its xor-4 /
+// xor-8 partner's value); only 32-lane rows need one exchange through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false);
+  return x + __int_as_float(y);
+}
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+  x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);                 // row_half_mirror
+  if (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror
+  if (LPR >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
 ckv_status validate(const ckv_params *p);
 void derive(const ckv_params *p, Shape *s);
 

@@ -74,15 +74,27 @@ __global__ void __launch_bounds__(256) vnorm_rows_kernel(VnormArgs a) {
   const char *base = a.v + b * a.vs_b + g * a.vs_h;
   const int sub = threadIdx.x % LPR, rloc = threadIdx.x / LPR;
   float local = 0.0f;
-  for (int r = rloc; r < kVnormRows; r += 256 / LPR) {
-    const int t = blk * kVnormRows + r;
-    float sq = 0.0f;
-    if (t < a.T) {
-      const chunk_t c = *reinterpret_cast<const chunk_t *>(base + (int64_t)t * a.vs_t + sub * 16);
+  constexpr int RPI = 256 / LPR;  // rows per step of the workgroup
+  constexpr int U = 8;            // steps whose loads are in flight together
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_v;
+  for (int r0 = rloc; r0 < kVnormRows; r0 += U * RPI) {
+    u32x4_v c[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = blk * kVnormRows + r0 + u * RPI;
+      c[u] = u32x4_v{0u, 0u, 0u, 0u};
+      // V is read once: streaming (non-temporal) loads
+      if (r0 + u * RPI < kVnormRows && t < a.T)
+        c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_v *>(base + (int64_t)t * a.vs_t + sub * 16));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = blk * kVnormRows + r0 + u * RPI;
+      float sq = 0.0f;
       if (DT == CKV_BF16) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t pair = c[e];
+          const uint32_t pair = c[u][e];
           const float lo = __uint_as_float(pair << 16);
           const float hi = __uint_as_float(pair & 0xffff0000u);
           sq = fmaf(lo, lo, sq);
@@ -91,18 +103,17 @@ __global__ void __launch_bounds__(256) vnorm_rows_kernel(VnormArgs a) {
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t word = c[e];
+          const uint32_t word = c[u][e];
           const float x = __uint_as_float(word);
           sq = fmaf(x, x, sq);
         }
       }
-    }
-#pragma unroll
-    for (int o = LPR / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
-    if (sub == 0 && t < a.T) {
-      const float nrm = sqrtf(sq);
-      a.ratio[(size_t)unit * a.T + t] = nrm;
-      local += nrm;
+      sq = row_sum<LPR>(sq);
+      if (sub == 0 && r0 + u * RPI < kVnormRows && t < a.T) {
+        const float nrm = sqrtf(sq);
+        a.ratio[(size_t)unit * a.T + t] = nrm;
+        local += nrm;
+      }
     }
   }
 #pragma unroll
