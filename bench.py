@@ -392,8 +392,9 @@ def main() -> int:
     dominant, dom_ms = ((("rowstats_lds_kernel" if bf16 else "rowstats_kernel"), ms_pass1)
                         if ms_pass1 >= ms_pass2 and not args.given_lse
                         else (("colsum_lds_kernel" if bf16 else "colsum_kernel"), ms_pass2))
+    pass2_has_v = args.value_norm and not args.unfused  # the fused call also reads V for the value norms
     scan_ms = {"rowstats+lse": round(ms_pass1, 4),
-               ("colsum" if args.unfused else "colsum+tables"): round(ms_pass2, 4)}
+               ("colsum" if args.unfused else "colsum+tables+vnorm" if pass2_has_v else "colsum+tables"): round(ms_pass2, 4)}
     if args.scan == "single_read" and not args.given_lse:
         # the persistent kernel does both passes in one launch: time the call as a whole
         whole = []
@@ -409,7 +410,11 @@ def main() -> int:
         dom_ms = sum(a.elapsed_time(b_) for a, b_ in whole) / len(whole)
         dominant = "fused_scan_kernel"
         scan_ms["single_read"] = round(dom_ms, 4)
-    achieved = scan_bytes(w) / (dom_ms * 1e-3) / 1e9
+    dom_bytes = scan_bytes(w)
+    if pass2_has_v and dominant.startswith("colsum"):
+        dominant += " + vnorm_rows_kernel"   # timed together: K and V are each read once in that region
+        dom_bytes += w.batch * w.n_kv_heads * w.seq_len * w.head_dim * (2 if bf16 else 4)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),

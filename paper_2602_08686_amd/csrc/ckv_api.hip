@@ -204,12 +204,12 @@ extern "C" ckv_status ckv_apply_tables(const ckv_params *params, const float *sc
 
 // Whether ckv_window_utility can run its fused second pass for this call (else it runs the two
 // unfused steps through the scratch buffer): the pipelined bf16 kernels with one 32-row tile per head
-// and all query tiles of a group in one wave, pooling kernels of at most 7 taps, no value norm, rows
-// that keep the 128-bit and 64-bit accesses aligned.
+// and all query tiles of a group in one wave, pooling kernels of at most 7 taps, rows that keep the
+// 128-bit and 64-bit accesses aligned. With the value-norm flag the ratio, which is common to a group's
+// heads and non-negative, multiplies the group maximum afterwards (in the value-norm scaling pass).
 static bool utility_fast_path(const ckv_params *p, const Shape &s, const float *scratch, const float *utility) {
   const int kernel = p->pool == CKV_POOL_NONE ? 1 : p->pool_kernel;
-  return p->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1 && !(p->flags & CKV_FLAG_VALUE_NORM) &&
-         kernel / 2 <= 3 && s.T % 4 == 0 && s.P % 4 == 0 && s.P > 0 && (uintptr_t)scratch % 16 == 0 &&
+  return p->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1 && kernel / 2 <= 3 && s.T % 4 == 0 && s.P % 4 == 0 && s.P > 0 && (uintptr_t)scratch % 16 == 0 &&
          (uintptr_t)utility % 16 == 0 && (int64_t)s.Hkv * s.P < (1 << 29);
 }
 
@@ -247,6 +247,8 @@ extern "C" ckv_status ckv_window_utility(const ckv_params *params, const void *q
       return CKV_EHIP;
     if (launch_utility_fixup(params, s2, scores_scratch, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,
                              utility, budget, tau, stream) != hipSuccess)
+      return CKV_EHIP;
+    if (vn && launch_value_norm(params, s, w, v, vnorm_ratio, (char *)workspace, stream, utility) != hipSuccess)
       return CKV_EHIP;
     return CKV_OK;
   }

@@ -109,8 +109,9 @@ hipError_t launch_utility_fixup(const ckv_params *p, const Shape &s, const float
                                 const float *w_head, const float *head_share, const float *t_gate, int n_ent,
                                 int n_ppl, const int32_t *risk_bins, float *utility, int32_t *budget, float *tau,
                                 hipStream_t stream);
+// utility_scaled: if given, [units][P] utilities that the scaling pass multiplies by the ratio
 hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspace &w, const void *v,
-                             float *ratio, char *ws, hipStream_t stream);
+                             float *ratio, char *ws, hipStream_t stream, float *utility_scaled = nullptr);
 hipError_t launch_apply_tables(const ckv_params *p, const Shape &s, const float *scores,
                                const float *vnorm_ratio, const float *w_head, const float *head_share,
                                const float *t_gate, int n_ent, int n_ppl, const int32_t *risk_bins,

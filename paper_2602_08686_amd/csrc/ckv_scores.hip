@@ -63,6 +63,8 @@ struct VnormArgs {
   int Hkv, T, n_blocks;
   float *ratio;  // [units][T]
   float *vsum;   // [units][n_blocks]
+  float *utility;  // [units][P] multiplied by the ratio in the scaling pass, or null
+  int P;
 };
 constexpr int kVnormRows = 1024;
 
@@ -131,12 +133,16 @@ __global__ void __launch_bounds__(256) vnorm_scale_kernel(VnormArgs a) {
   const float inv = 1.0f / (total / (float)a.T + kValueNormEps);
   for (int r = threadIdx.x; r < kVnormRows; r += 256) {
     const int t = blk * kVnormRows + r;
-    if (t < a.T) a.ratio[(size_t)unit * a.T + t] *= inv;
+    if (t < a.T) {
+      const float rho = a.ratio[(size_t)unit * a.T + t] * inv;
+      a.ratio[(size_t)unit * a.T + t] = rho;
+      if (a.utility && t < a.P) a.utility[(size_t)unit * a.P + t] *= rho;
+    }
   }
 }
 
 hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspace &w, const void *v,
-                             float *ratio, char *ws, hipStream_t stream) {
+                             float *ratio, char *ws, hipStream_t stream, float *utility_scaled) {
   VnormArgs a;
   a.v = (const char *)v;
   a.vs_b = p->v_stride[0] * s.esize;
@@ -147,6 +153,8 @@ hipError_t launch_value_norm(const ckv_params *p, const Shape &s, const Workspac
   a.n_blocks = vnorm_blocks_per_unit(s);
   a.ratio = ratio;
   a.vsum = (float *)(ws + w.vsum_off);
+  a.utility = utility_scaled;
+  a.P = s.P;
   const dim3 grid(a.n_blocks, s.Bz * s.Hkv), block(256);
   if (p->dtype == CKV_BF16) {
     if (s.d == 128) hipLaunchKernelGGL((vnorm_rows_kernel<CKV_BF16, 128>), grid, block, 0, stream, a);
