@@ -205,7 +205,7 @@ ckv_status ckv_window_utility(const ckv_params *params, const void *q_win, const
  *   tau      in   [Bz] fp32                       on the device)
  *   idx      out  [Bz,Hkv,cap] int32; entries at and beyond count[b,g] are not written
  *   count    out  [Bz,Hkv] int32
- *   workspace     optional (NULL allowed). Up to 65536 prefix positions it is not used. Beyond that,
+ *   workspace     optional (NULL allowed). Up to 32768 prefix positions it is not used. Beyond that,
  *                 with ckv_workspace_bytes(params) bytes (256-byte aligned; CKV_EWORKSPACE if
  *                 misaligned or smaller) a unit's positions are split over several workgroups, which is
  *                 several times faster for long contexts with few (batch, head) units; the result is

@@ -271,8 +271,8 @@ extern "C" ckv_status ckv_select_topk(const ckv_params *params, const float *uti
   if (!utility || !budget || !tau || !idx || !count) return CKV_EINVAL;
   Shape s;
   derive(params, &s);
-  // Optional: up to 65536 prefix positions the selection keeps everything on chip; beyond that a
-  // workspace lets it split a unit over several workgroups.
+  // Optional: short prefixes are selected by one workgroup per unit, everything on chip; for long ones a
+  // workspace lets the selection split a unit over several workgroups.
   Workspace w;
   layout(params, s, &w);
   const bool split = workspace && w.select_bytes > 0;

@@ -317,8 +317,7 @@ __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a
 }
 
 // ---------------------------------------------------------------------------------------------
-// Split select: prefixes beyond the register kernel's 65536 positions, when the caller passes a
-// workspace. A unit's positions are cut into slices of 8192, one workgroup each, so that long contexts
+// Split select: prefixes beyond 32768 positions, when the caller passes a workspace. A unit's positions are cut into slices of 8192, one workgroup each, so that long contexts
 // with few (batch, head) units still fill the chip. Five launches walk the same steps as the register
 // kernel: three digit histograms (slices merge theirs into the unit's histogram in global memory with
 // integer atomics: order-independent, so the result is deterministic), the slices' counts of keys above
@@ -333,7 +332,7 @@ struct SplitArgs {
   SelectArgs a;
   int *hist;       // [units][kSplitHist], zero before the first phase
   int *slice_cnt;  // [units][S] keys above | equal << 16 of each slice
-  int *thr;        // [units][4] threshold key, need_eq
+  int *thr;        // [units][4 phases][4] digits found so far, keys still needed, state
   int S;           // slices per unit
 };
 
@@ -377,11 +376,19 @@ __global__ void __launch_bounds__(kSelectThreads) select_split_kernel(SplitArgs 
     }
   }
 
-  // Threshold digits from the histograms merged by the earlier phases (same arithmetic in every
-  // workgroup of the unit).
+  // Threshold digits: phase p finds digit p - 1 from the histogram that phase p - 1 merged (the same
+  // arithmetic in every workgroup of the unit) and takes the digits before it from the record that
+  // the previous phase's first slice left; records are per phase, so no workgroup reads one that is
+  // being written in its own launch.
   int state = 1, k = max(kp, 1);
   uint32_t prefix = 0u;
-  if constexpr (PHASE >= 1 && PHASE <= 3) {
+  int *rec = sa.thr + (size_t)unit * 16;  // [phase][prefix, k, state, -]
+  if constexpr (PHASE >= 2) {
+    prefix = (uint32_t)rec[4 * (PHASE - 1) + 0];
+    k = rec[4 * (PHASE - 1) + 1];
+    state = rec[4 * (PHASE - 1) + 2];
+  }
+  if constexpr (PHASE == 1) {
     for (int i = tid; i < 2048; i += kSelectThreads) hist[i] = gh[i];
     __syncthreads();
     if (wave == 0) {
@@ -396,23 +403,28 @@ __global__ void __launch_bounds__(kSelectThreads) select_split_kernel(SplitArgs 
     state = s_state;
     prefix = s_prefix;
     k = s_k;
-#pragma unroll
-    for (int level = 1; level <= 2; ++level) {
-      if (PHASE > level && state == 1) {
-        __syncthreads();  // everyone has read s_prefix / s_k and wave 0 is done with hist
-        hist[tid] = gh[2048 + 1024 * (level - 1) + tid];
-        __syncthreads();
-        if (wave == 0) {
-          const BinResult r = find_bin<1024>(hist, k, lane);
-          if (lane == 0) {
-            s_prefix = (prefix << 10) | (uint32_t)r.bin;
-            s_k = k - r.above;
-          }
+  }
+  if constexpr (PHASE == 2 || PHASE == 3) {
+    if (state == 1) {
+      hist[tid] = gh[2048 + 1024 * (PHASE - 2) + tid];
+      __syncthreads();
+      if (wave == 0) {
+        const BinResult r = find_bin<1024>(hist, k, lane);
+        if (lane == 0) {
+          s_prefix = (prefix << 10) | (uint32_t)r.bin;
+          s_k = k - r.above;
         }
-        __syncthreads();
-        prefix = s_prefix;
-        k = s_k;
       }
+      __syncthreads();
+      prefix = s_prefix;
+      k = s_k;
+    }
+  }
+  if constexpr (PHASE >= 1 && PHASE <= 3) {
+    if (slice == 0 && tid == 0) {
+      rec[4 * PHASE + 0] = (int)prefix;
+      rec[4 * PHASE + 1] = k;
+      rec[4 * PHASE + 2] = state;
     }
   }
 
@@ -434,12 +446,8 @@ __global__ void __launch_bounds__(kSelectThreads) select_split_kernel(SplitArgs 
 
   if constexpr (PHASE == 3) {
     uint32_t thr = 0u;  // keep-all: every candidate has k' > 0
-    int need_eq = 0;
     if (state == 2) thr = 0xffffffffu;
-    else if (state == 1) {
-      thr = prefix;
-      need_eq = k;
-    }
+    else if (state == 1) thr = prefix;
     int c = 0;
 #pragma unroll
     for (int j = 0; j < kSplitNV; ++j)
@@ -453,17 +461,18 @@ __global__ void __launch_bounds__(kSelectThreads) select_split_kernel(SplitArgs 
       int tot = 0;  // 8192 positions a slice: neither half overflows
       for (int w = 0; w < kSelectThreads / kWave; ++w) tot += s_red[w];
       sa.slice_cnt[(size_t)unit * sa.S + slice] = tot;
-      if (slice == 0) {
-        sa.thr[unit * 4 + 0] = (int)thr;
-        sa.thr[unit * 4 + 1] = need_eq;
-      }
     }
     return;
   }
 
   if constexpr (PHASE == 4) {
-    const uint32_t thr = (uint32_t)sa.thr[unit * 4 + 0];
-    const int need_eq = sa.thr[unit * 4 + 1];
+    uint32_t thr = 0u;  // as in phase 3, from its record
+    int need_eq = 0;
+    if (state == 2) thr = 0xffffffffu;
+    else if (state == 1) {
+      thr = prefix;
+      need_eq = k;
+    }
     int base_gt = 0, base_eq = 0, all_gt = 0, all_eq = 0;
     for (int i = 0; i < sa.S; ++i) {  // same address in every lane: one broadcast load each
       const int c = sa.slice_cnt[(size_t)unit * sa.S + i];
@@ -485,9 +494,10 @@ __global__ void __launch_bounds__(kSelectThreads) select_split_kernel(SplitArgs 
 }
 
 size_t select_workspace_bytes(const Shape &s) {
-  if (s.P <= 16 * 4 * kSelectThreads || s.P % 4 != 0) return 0;  // the register kernel or the streaming one
+  // up to 32768 positions the register kernel (one workgroup per unit, one launch) is the faster one
+  if (s.P <= 8 * 4 * kSelectThreads || s.P % 4 != 0) return 0;
   const size_t units = (size_t)s.Bz * s.Hkv, S = (s.P + kSplitSlice - 1) / kSplitSlice;
-  return units * (kSplitHist + S + 4) * sizeof(int);
+  return units * (kSplitHist + S + 16) * sizeof(int);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -659,12 +669,8 @@ hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utili
   const dim3 grid(s.Bz * s.Hkv), block(kSelectThreads);
   const int vectors = (s.P + 4 * kSelectThreads - 1) / (4 * kSelectThreads);  // 128-bit loads per thread
   const bool aligned = s.P % 4 == 0 && (uintptr_t)utility % 16 == 0 && s.P > 0;
-  if (aligned && vectors <= 1) hipLaunchKernelGGL(select_reg_kernel<1>, grid, block, 0, stream, a);
-  else if (aligned && vectors <= 2) hipLaunchKernelGGL(select_reg_kernel<2>, grid, block, 0, stream, a);
-  else if (aligned && vectors <= 4) hipLaunchKernelGGL(select_reg_kernel<4>, grid, block, 0, stream, a);
-  else if (aligned && vectors <= 8) hipLaunchKernelGGL(select_reg_kernel<8>, grid, block, 0, stream, a);
-  else if (aligned && vectors <= 16) hipLaunchKernelGGL(select_reg_kernel<16>, grid, block, 0, stream, a);
-  else if (aligned && ws && select_workspace_bytes(s) > 0) {
+  const bool split = aligned && ws && select_workspace_bytes(s) > 0;
+  if (split) {
     SplitArgs sa;
     sa.a = a;
     sa.S = (s.P + kSplitSlice - 1) / kSplitSlice;
@@ -681,7 +687,12 @@ hipError_t launch_select(const ckv_params *p, const Shape &s, const float *utili
     hipLaunchKernelGGL(select_split_kernel<2>, split_grid, block, 0, stream, sa);
     hipLaunchKernelGGL(select_split_kernel<3>, split_grid, block, 0, stream, sa);
     hipLaunchKernelGGL(select_split_kernel<4>, split_grid, block, 0, stream, sa);
-  } else hipLaunchKernelGGL(select_kernel, grid, block, 0, stream, a);
+  } else if (aligned && vectors <= 1) hipLaunchKernelGGL(select_reg_kernel<1>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 2) hipLaunchKernelGGL(select_reg_kernel<2>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 4) hipLaunchKernelGGL(select_reg_kernel<4>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 8) hipLaunchKernelGGL(select_reg_kernel<8>, grid, block, 0, stream, a);
+  else if (aligned && vectors <= 16) hipLaunchKernelGGL(select_reg_kernel<16>, grid, block, 0, stream, a);
+  else hipLaunchKernelGGL(select_kernel, grid, block, 0, stream, a);
   return hipGetLastError();
 }
 
