@@ -100,8 +100,10 @@ def layer_shared_bench(args, w, n_layers, torch, B, wl) -> int:
     tables = wl.make_tables(w, dev)
     layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
     q0, k0, v0 = layers[0]["q"], layers[0]["k"], layers[0]["v"]
+    # group masses (sums over each KV head's query heads) are all that alpha needs
+    flags = B.FLAG_VALUE_NORM | (B.FLAG_GROUP_MASS if w.dtype == "bf16" and w.window <= 32 and w.group <= 4 else 0)
     params = [B.params_for(q0, k0, v0, pool=w.pool, pool_kernel=w.pool_kernel, budget=w.budget, cap=w.cap,
-                           layer=l % w.n_layers, n_layers=w.n_layers, flags=B.FLAG_VALUE_NORM) for l in range(n_layers)]
+                           layer=l % w.n_layers, n_layers=w.n_layers, flags=flags) for l in range(n_layers)]
     one = B.make_params(batch=w.batch, n_q_heads=1, n_kv_heads=1, head_dim=w.head_dim, seq_len=w.seq_len,
                         window=w.window, dtype=w.dtype, pool=wl.POOL_NONE, pool_kernel=1, budget=w.budget, cap=w.cap,
                         n_layers=w.n_layers)
@@ -150,6 +152,7 @@ def layer_shared_bench(args, w, n_layers, torch, B, wl) -> int:
         "config": {"workload": w.name, "mode": "layer_shared (Alg. 1 as printed)", "layers_per_step": n_layers,
                    "batch": w.batch, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "seq_len": w.seq_len, "window": w.window, "budget_per_layer": w.budget, "value_norm": True,
+                   "group_mass": bool(flags & B.FLAG_GROUP_MASS),
                    "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
         "roofline": None,
     }

@@ -55,7 +55,13 @@ enum {
    * ignored where it does not exist; TWO_KERNELS names the default explicitly. At most one may be
    * set.                                                                                            */
   CKV_FLAG_SCAN_TWO_KERNELS = 2u,
-  CKV_FLAG_SCAN_SINGLE_READ = 4u
+  CKV_FLAG_SCAN_SINGLE_READ = 4u,
+  /* Layer-shared mode only (paper Eq. 4: alpha is a mean over heads): ckv_window_scores writes, instead
+   * of every query head's mass, the SUM over the query heads of each KV head, scores [Bz,Hkv,T], and
+   * ckv_alpha_accumulate reads that layout -- a quarter of the bytes for groups of four. Exists for
+   * bf16 with W <= 32 and G <= 4 (CKV_EUNSUPPORTED otherwise); excludes SCAN_SINGLE_READ; rejected by
+   * the calls that need per-head masses (ckv_apply_tables, ckv_window_utility).                      */
+  CKV_FLAG_GROUP_MASS = 8u
 };
 
 /* Problem description shared by all calls. Plain data; the caller may reuse or free it after a call. */
@@ -236,7 +242,8 @@ ckv_status ckv_compact_kv(const ckv_params *params, const void *k, const void *v
  *   for each layer: ckv_shared_utility, ckv_select_topk with a one-head ckv_params (batch, 1 query head,
  *                   1 KV head, budget = B_l; utility [Bz,1,P], budget [Bz,1]), ckv_compact_kv_shared.
  *
- * ckv_alpha_accumulate: alpha[b,t] += weight * sum_h scores[b,h,t]. With weight = 1/(L*Hq) over all
+ * ckv_alpha_accumulate: alpha[b,t] += weight * sum_h scores[b,h,t] (with CKV_FLAG_GROUP_MASS: the sum
+ * over the Hkv rows of the group-mass layout). With weight = 1/(L*Hq) over all
  * layers this is alpha = (T/W) sum_{j in Omega} Abar[j,:] for Abar the mean of A over layers and heads
  * (paper Eq. 4, Alg. 1 (A)); sum_t alpha = T.
  *   scores  in      [Bz,Hq,T] fp32 of one layer (from ckv_window_scores)

@@ -20,6 +20,7 @@ POOL_NONE, POOL_AVG, POOL_MAX = 0, 1, 2
 FLAG_VALUE_NORM = 1
 FLAG_SCAN_TWO_KERNELS = 2   # force the scan that streams K twice
 FLAG_SCAN_SINGLE_READ = 4   # force the persistent scan that reads K once (where it exists)
+FLAG_GROUP_MASS = 8         # ckv_window_scores writes per-KV-head sums [Bz,Hkv,T] (layer-shared mode)
 
 EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_alpha_accumulate", "ckv_risk_struct", "ckv_shared_utility", "ckv_compact_kv_shared",

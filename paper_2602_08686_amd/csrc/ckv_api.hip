@@ -21,9 +21,11 @@ ckv_status validate(const ckv_params *p) {
   if (p->pool != CKV_POOL_NONE && (p->pool_kernel < 1 || p->pool_kernel > 63 || p->pool_kernel % 2 == 0))
     return CKV_EINVAL;
   if (p->budget_per_kv_head < p->window) return CKV_EINVAL;
-  if (p->flags & ~(uint32_t)(CKV_FLAG_VALUE_NORM | CKV_FLAG_SCAN_TWO_KERNELS | CKV_FLAG_SCAN_SINGLE_READ))
+  if (p->flags & ~(uint32_t)(CKV_FLAG_VALUE_NORM | CKV_FLAG_SCAN_TWO_KERNELS | CKV_FLAG_SCAN_SINGLE_READ |
+                             CKV_FLAG_GROUP_MASS))
     return CKV_EINVAL;
   if ((p->flags & CKV_FLAG_SCAN_TWO_KERNELS) && (p->flags & CKV_FLAG_SCAN_SINGLE_READ)) return CKV_EINVAL;
+  if ((p->flags & CKV_FLAG_GROUP_MASS) && (p->flags & CKV_FLAG_SCAN_SINGLE_READ)) return CKV_EINVAL;
   if (p->head_dim < 1) return CKV_EINVAL;
   const int64_t b_tot = (int64_t)p->budget_per_kv_head * p->n_kv_heads;
   int64_t need = b_tot - (int64_t)(p->n_kv_heads - 1) * p->window;
@@ -158,6 +160,9 @@ extern "C" ckv_status ckv_window_scores(const ckv_params *params, const void *q_
   layout(params, s, &w);
   st = workspace_ok(w, workspace, workspace_bytes);
   if (st != CKV_OK) return st;
+  // the group-mass output exists where one wave holds all query heads of a KV head, one tile each
+  if ((params->flags & CKV_FLAG_GROUP_MASS) && !(params->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1))
+    return CKV_EUNSUPPORTED;
   hipStream_t stream = (hipStream_t)hip_stream;
   if (launch_window_scores(params, s, w, q_win, k, lse, nullptr, scores, (char *)workspace, stream) != hipSuccess)
     return CKV_EHIP;
@@ -192,6 +197,7 @@ extern "C" ckv_status ckv_apply_tables(const ckv_params *params, const float *sc
   ckv_status st = validate(params);
   if (st != CKV_OK) return st;
   if (!scores || !w_head || !utility || !budget || !tau) return CKV_EINVAL;
+  if (params->flags & CKV_FLAG_GROUP_MASS) return CKV_EINVAL;  // needs per-head masses
   if ((params->flags & CKV_FLAG_VALUE_NORM) && !vnorm_ratio) return CKV_EINVAL;
   if (t_gate && (n_ent < 1 || n_ppl < 1 || !risk_bins)) return CKV_EINVAL;
   Shape s;
@@ -222,6 +228,7 @@ extern "C" ckv_status ckv_window_utility(const ckv_params *params, const void *q
   ckv_status st = validate(params);
   if (st != CKV_OK) return st;
   if (!q_win || !k || !scores_scratch || !w_head || !utility || !budget || !tau) return CKV_EINVAL;
+  if (params->flags & CKV_FLAG_GROUP_MASS) return CKV_EINVAL;  // needs per-head masses
   const bool vn = params->flags & CKV_FLAG_VALUE_NORM;
   if (vn && (!v || !vnorm_ratio)) return CKV_EINVAL;
   if (t_gate && (n_ent < 1 || n_ppl < 1 || !risk_bins)) return CKV_EINVAL;
@@ -303,7 +310,8 @@ extern "C" ckv_status ckv_alpha_accumulate(const ckv_params *params, const float
   if (!scores || !alpha || !isfinite(weight)) return CKV_EINVAL;
   Shape s;
   derive(params, &s);
-  if (launch_alpha_accumulate(s, scores, weight, alpha, (hipStream_t)hip_stream) != hipSuccess) return CKV_EHIP;
+  const int rows = (params->flags & CKV_FLAG_GROUP_MASS) ? s.Hkv : s.Hq;  // rows of scores per batch element
+  if (launch_alpha_accumulate(s, rows, scores, weight, alpha, (hipStream_t)hip_stream) != hipSuccess) return CKV_EHIP;
   return CKV_OK;
 }
 

@@ -126,7 +126,7 @@ hipError_t launch_gather(const ckv_params *p, const Shape &s, const void *k, con
                          const int32_t *idx, const int32_t *count, void *k_out, void *v_out,
                          hipStream_t stream, bool shared_list = false);
 // layer-shared mode (Alg. 1 as printed)
-hipError_t launch_alpha_accumulate(const Shape &s, const float *scores, float weight, float *alpha,
+hipError_t launch_alpha_accumulate(const Shape &s, int rows, const float *scores, float weight, float *alpha,
                                    hipStream_t stream);
 hipError_t launch_risk_struct(const Shape &s, const float *alpha, const float *edges, int n_edges, float *risk,
                               int32_t *bin, hipStream_t stream);

@@ -40,7 +40,8 @@ struct ScoreArgs {
   float2 *part;      // [unit][group][NQ*32][n_chunks] (max, sum) in the log2 domain
   const float *lse;  // [Bz][Hq][W] natural log
   float *lse_out;
-  float *scores;     // [Bz][Hq][T]
+  float *scores;     // [Bz][Hq][T]; with group_sum: [Bz][Hkv][T], the sum over each KV head's query heads
+  int group_sum;
   // fused utility form of pass 2 only
   const float *w_row;  // w_head + layer * Hq
   float *utility;      // [Bz][Hkv][P]
@@ -702,6 +703,17 @@ __device__ __forceinline__ void store_column_sums(const ScoreArgs &a, const Bloc
   }
 }
 
+// Group-sum form of the same: one value per key, the sum over the group's heads.
+template <int NQ>
+__device__ __forceinline__ void store_group_sum(const ScoreArgs &a, const BlockCoord &bc, const float (&cs)[NQ], int kt,
+                                                int hh) {
+  float x = cs[0];  // padding heads have zero query rows and bias -1000: their weights are exactly 0
+#pragma unroll
+  for (int i = 1; i < NQ; ++i) x += cs[i];
+  const float tot = (x + __shfl_xor(x, 32)) * a.norm;
+  if (hh == 0 && kt < a.T) a.scores[((size_t)bc.b * a.Hkv + bc.g) * a.T + kt] = tot;
+}
+
 // Pipeline form of the same: the totals of one key tile go to a per-wave LDS stage
 // [head of the group][key of the ring cycle], and once per ring cycle (4 tiles, 128 keys) every lane
 // stores four consecutive keys of one head with one 128-bit buffer store per pair of heads.
@@ -740,6 +752,28 @@ __device__ __forceinline__ void flush_column_sums(const ScoreArgs &a, const Bloc
     typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, 0);
   }
+}
+
+// Group-sum form of the flush (layer-shared mode: the prompt's alpha is a mean over heads, so only the
+// sum over a KV head's query heads is needed): lanes 0..31 add the even heads of the stage, lanes
+// 32..63 the odd ones, four consecutive keys each; the halves are added and lanes 0..31 store one
+// 128-bit piece of the single output row -- a quarter of the per-head form's bytes for groups of four.
+template <int NQ>
+__device__ __forceinline__ void flush_group_sums(const ScoreArgs &a, const BlockCoord &bc, const float *stage,
+                                                 int t_first, int lane, __amdgpu_buffer_rsrc_t rsrc_g) {
+  const int half = lane >> 5, key4 = 4 * (lane & 31);
+  const int heads_left = a.G - bc.grp * NQ;
+  f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int h = 0; h < NQ; h += 2) {
+    const int mine = h + half;
+    if (mine < NQ && mine < heads_left) acc += *reinterpret_cast<const f32x4 *>(stage + mine * (kRing * kTile) + key4);
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], 32);
+  const uint32_t off = half == 0 ? (uint32_t)((bc.g * a.T + t_first + key4) * 4) : 0x80000000u;
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, acc), rsrc_g, off, 0, 0);
 }
 
 // Fused form of the flush (ckv_window_utility): instead of the column sums, the wave writes the
@@ -854,8 +888,9 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
   }
 }
 
-template <int DT, int DH, int NQ, int WT, bool UTIL = false>
+template <int DT, int DH, int NQ, int WT, bool UTIL = false, bool GSUM = false>
 __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArgs a) {
+  static_assert(!(UTIL && GSUM) && (!GSUM || WT == 1), "one epilogue at a time; group sums take one tile per head");
   static_assert(NQ % WT == 0, "whole heads");
   using G = Geom<DT, DH>;
   constexpr int NCH = G::NCH;
@@ -882,14 +917,16 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
   // Descriptor over scores[b]: Hq * T floats (the host checks that this stays below 2 GiB). Lanes with
   // nothing to store present an offset outside it, which the hardware drops: no branch splits the
   // pipeline's code, and every flush issues exactly N_STORES store instructions.
+  const int score_rows = GSUM ? a.Hkv : a.Hq;  // rows of a batch element in the output
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void *)(a.scores + (size_t)bc.b * a.Hq * a.T), 0, a.Hq * a.T * 4, 0x00020000);
+      (void *)(a.scores + (size_t)bc.b * score_rows * a.T), 0, score_rows * a.T * 4, 0x00020000);
   // Vector memory operations complete in issue order, stores included. When tile t + 1 is picked up,
   // the loads of tiles t + 2 and t + 3 were issued after its own, and so were the stores of the
   // previous ring cycle if t is the cycle's first or second tile; that many operations may still be
   // in flight. The first cycle has no such stores behind it: dropped stores (offset outside the
   // descriptor) issued after the first loads stand in.
-  constexpr int N_STORES = (NQ / WT + 1) / 2 + (UTIL ? 1 : 0);  // per flush; the fused form adds the utility store
+  // per flush; the fused form adds the utility store, the group-sum form has a single store
+  constexpr int N_STORES = GSUM ? 1 : (NQ / WT + 1) / 2 + (UTIL ? 1 : 0);
   __shared__ __attribute__((aligned(16))) float s_stage[kScoreWaves][(NQ / WT) * (UTIL ? kUtilRow : kRing * kTile)];
   // fused form: descriptor over utility[b] (Hkv * P floats) and the weights of this group's heads
   const __amdgpu_buffer_rsrc_t rsrc_u = __builtin_amdgcn_make_buffer_rsrc(
@@ -943,6 +980,7 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
     }
     if constexpr (UTIL)
       flush_utility<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, t0 == 0, t0 + kRing >= n_piped, lane, rsrc, rsrc_u, wgt);
+    else if constexpr (GSUM) flush_group_sums<NQ>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
     else flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
   }
   wait_vm<0>();
@@ -959,7 +997,8 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
       bias[i].add(acc[0], ones);
       cs[i] = colsum_weights<true>(acc[0], a.c2, hh, kt - a.P - j0);
     }
-    store_column_sums<NQ>(a, bc, cs, WT, kt, hh);
+    if constexpr (GSUM) store_group_sum<NQ>(a, bc, cs, kt, hh);
+    else store_column_sums<NQ>(a, bc, cs, WT, kt, hh);
   }
 }
 
@@ -986,6 +1025,7 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
     // NQ is a multiple of WT (whole heads per wave)
     if (s.WT == 1) {
       if (a.utility) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1, true>), grid, block, 0, stream, a);
+      else if (a.group_sum) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1, false, true>), grid, block, 0, stream, a);
       else hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1>), grid, block, 0, stream, a);
       return;
     }

@@ -12,7 +12,7 @@ namespace ckv {
 typedef __attribute__((ext_vector_type(4))) float f32x4_s;
 
 struct AlphaArgs {
-  const float *scores;  // [Bz][Hq][T]
+  const float *scores;  // [Bz][Hq][T] (Hq = rows per batch element: query heads, or KV heads of group masses)
   float *alpha;         // [Bz][T], read and written
   float weight;
   int Hq, T;
@@ -120,13 +120,13 @@ __global__ void __launch_bounds__(256) shared_utility_kernel(SharedUtilArgs a) {
   a.utility[(size_t)b * a.P + t] = best;
 }
 
-hipError_t launch_alpha_accumulate(const Shape &s, const float *scores, float weight, float *alpha,
+hipError_t launch_alpha_accumulate(const Shape &s, int rows, const float *scores, float weight, float *alpha,
                                    hipStream_t stream) {
   AlphaArgs a;
   a.scores = scores;
   a.alpha = alpha;
   a.weight = weight;
-  a.Hq = s.Hq;
+  a.Hq = rows;
   a.T = s.T;
   const bool vec = s.T % 4 == 0 && (uintptr_t)scores % 16 == 0 && (uintptr_t)alpha % 16 == 0;
   if (vec) hipLaunchKernelGGL(alpha_accumulate_kernel<true>, dim3((s.T / 4 + 255) / 256, s.Bz), dim3(256), 0, stream, a);

@@ -59,7 +59,8 @@ def test_workspace_bytes_is_aligned_and_scales():
     dict(budget=16),                   # B < W
     dict(cap=100),                     # cap below the largest possible per-head budget
     dict(layer=1, n_layers=1),
-    dict(flags=8),
+    dict(flags=16),                    # unknown flag
+    dict(flags=8 | 4),                 # group masses exclude the single-read scan
     dict(softmax_scale=-1.0),
     dict(k_stride=(4096 * 128 * 2, 4096 * 128, 127)),   # row stride < head_dim / misaligned
     dict(q_stride=(8 * 32 * 128, 32 * 128 + 4, 128)),   # not 16-byte aligned
@@ -192,6 +193,25 @@ def test_decode_consumer_entry_points_are_validated_on_the_host():
     for name in ("lf", "lk", "mass"):
         assert dm(**{name: None}) == B.CKV_EINVAL
     assert dm(n_q=0) == B.CKV_EINVAL
+
+
+def test_group_mass_flag_is_validated_on_the_host():
+    lib = B.load()
+    ref = ctypes.byref
+    d = ctypes.c_void_p(256)
+    p = _good(flags=B.FLAG_GROUP_MASS)
+    need = B.ckv_workspace_bytes(p)
+    assert need > 0
+    # the calls that need per-head masses reject the flag
+    assert lib.ckv_apply_tables(ref(p), d, None, d, None, None, 0, 0, None, d, d, d, None) == B.CKV_EINVAL
+    assert lib.ckv_window_utility(ref(p), d, d, None, None, d, None, None, 0, 0, None, d, None, d, d, d, d, need,
+                                  None) == B.CKV_EINVAL
+    # shapes without the group-mass form: f32, W > 32, more than four heads per KV head
+    for kw in (dict(dtype=torch.float32, head_dim=64), dict(window=64, budget=256), dict(n_q_heads=16, n_kv_heads=2)):
+        q = _good(flags=B.FLAG_GROUP_MASS, **kw)
+        n = B.ckv_workspace_bytes(q)
+        assert n > 0
+        assert lib.ckv_window_scores(ref(q), d, d, None, None, d, None, d, n, None) == B.CKV_EUNSUPPORTED
 
 
 def test_missing_library_fails_loudly(tmp_path):

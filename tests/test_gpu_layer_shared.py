@@ -153,3 +153,42 @@ def test_layer_shared_full_size_two_layers_of_c3():
         assert_scores_close(gu[b:b + 1], ref["utility"].astype(np.float64), f"shared utility of batch element {b}")
         assert_index_sets_match(gi[b:b + 1, None, :], gc[b:b + 1, None], ref["idx"][:, None, :], ref["count"][:, None],
                                 ref["utility"][:, None, :], ref["tau"], budget.cpu().numpy()[b:b + 1], W)
+
+
+GROUP_MASS_CASES = [
+    _case("gm_gqa4", "bf16", 2, 8, 2, 128, 4133, 32, 2, 300, pareto_frac=0.05),          # ragged tail
+    _case("gm_gqa3_long", "bf16", 1, 3, 1, 128, 140003, 32, 2, 300, sink_scale=8.0),      # three heads, whole pipeline rounds
+    _case("gm_mha_d64", "bf16", 1, 4, 4, 64, 70003, 17, 2, 200),                          # one head per group
+    _case("gm_gqa2_w1", "bf16", 2, 4, 2, 128, 500, 1, 2, 40),
+]
+
+
+@pytest.mark.parametrize("w", GROUP_MASS_CASES, ids=lambda w: w.name)
+def test_group_mass_scan_equals_the_sum_over_the_group_heads(w):
+    """CKV_FLAG_GROUP_MASS: the scan writes [Bz,Hkv,T] sums over each KV head's query heads; alpha built from
+    them equals alpha built from the per-head masses, and both match the oracle."""
+    print(f"case {w.name}", flush=True)
+    L, Bz, Hq, Hkv, T, G = w.n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.group
+    layers = [wl.make_layer(w, l, DEV) for l in range(L)]
+    alpha_g, alpha_h = torch.zeros(Bz, T, device=DEV), torch.zeros(Bz, T, device=DEV)
+    ref_maps = []
+    for l, t in enumerate(layers):
+        ph = params_of(w, t["q"], t["k"], t["v"], layer=l)
+        pg = params_of(w, t["q"], t["k"], t["v"], layer=l, flags=B.FLAG_GROUP_MASS)
+        buf = B.LayerBuffers(ph, DEV)
+        mass = torch.full((Bz, Hkv, T), float("nan"), device=DEV)
+        B.ckv_window_scores(ph, t["q"], t["k"], None, None, buf.scores, None, buf.workspace)
+        B.ckv_window_scores(pg, t["q"], t["k"], None, None, mass, None, buf.workspace)
+        B.ckv_alpha_accumulate(ph, buf.scores, 1.0 / (L * Hq), alpha_h)
+        B.ckv_alpha_accumulate(pg, mass, 1.0 / (L * Hq), alpha_g)
+        torch.cuda.synchronize()
+        ref = oracle.window_scores(f32(t["q"]), f32(t["k"]))
+        ref_maps.append(ref)
+        gm = mass.cpu().numpy()
+        assert_scores_close(gm, ref.reshape(Bz, Hkv, G, T).sum(2), "group mass")
+        per_head = buf.scores.cpu().numpy().astype(np.float64).reshape(Bz, Hkv, G, T).sum(2)
+        np.testing.assert_allclose(gm, per_head, rtol=1e-6, atol=0)        # same column sums, added in another order
+        np.testing.assert_allclose(gm.astype(np.float64).sum(-1), G * T, rtol=2e-4)
+    ref_alpha = oracle.alpha_mean(ref_maps)
+    assert_scores_close(alpha_g.cpu().numpy(), ref_alpha, "alpha from group masses")
+    np.testing.assert_allclose(alpha_g.cpu().numpy(), alpha_h.cpu().numpy(), rtol=2e-6, atol=0)
