@@ -39,6 +39,7 @@ struct ScoreArgs {
   float norm;   // T / W
   float2 *part;      // [unit][group][NQ*32][n_chunks] (max, sum) in the log2 domain
   const float *lse;  // [Bz][Hq][W] natural log
+  int lse_from_part; // pass 2 merges the row partials of pass 1 itself (no lse_kernel in between)
   float *lse_out;
   float *scores;     // [Bz][Hq][T]; with group_sum: [Bz][Hkv][T], the sum over each KV head's query heads
   int group_sum;
@@ -226,7 +227,16 @@ __global__ void __launch_bounds__(kScoreWaves *kWave, 2) rowstats_kernel(ScoreAr
   store_row_partials<NQ>(a, bc, wave, m, hh, rm, rl);
 }
 
-// One thread per (unit, group, tile row): LSE_j = ln2 * (M + log2 sum_c l_c 2^(m_c - M)).
+// LSE_j = ln2 * (M + log2 sum_c l_c 2^(m_c - M)) from the n_chunks partials of one row, in chunk order.
+__device__ __forceinline__ float merge_row_partials(const float2 *p, int n_chunks) {
+  float M = -1e30f;
+  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, p[c].x);
+  float L = 0.0f;
+  for (int c = 0; c < n_chunks; ++c) L += p[c].y * __builtin_amdgcn_exp2f(p[c].x - M);
+  return (M + __log2f(L)) * kLn2;
+}
+
+// One thread per (unit, group, tile row).
 template <int NQ>
 __global__ void lse_kernel(ScoreArgs a, int n_rows_total) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
@@ -238,13 +248,8 @@ __global__ void lse_kernel(ScoreArgs a, int n_rows_total) {
   const int tile = grp * NQ + in_group / kTile;
   const int j = (tile % a.WT) * kTile + in_group % kTile;
   if (tile >= a.n_tiles || j >= a.W) return;
-  const float2 *p = a.part + (size_t)row * a.n_chunks;
-  float M = -1e30f;
-  for (int c = 0; c < a.n_chunks; ++c) M = fmaxf(M, p[c].x);
-  float L = 0.0f;
-  for (int c = 0; c < a.n_chunks; ++c) L += p[c].y * __builtin_amdgcn_exp2f(p[c].x - M);
   const int b = unit / a.Hkv, g = unit % a.Hkv, h = g * a.G + tile / a.WT;
-  a.lse_out[((size_t)b * a.Hq + h) * a.W + j] = (M + __log2f(L)) * kLn2;
+  a.lse_out[((size_t)b * a.Hq + h) * a.W + j] = merge_row_partials(a.part + (size_t)row * a.n_chunks, a.n_chunks);
 }
 
 // One 32-row x 32-key tile of pass 2 for the plain kernel. The accumulator starts at -LSE_row / scale
@@ -911,7 +916,15 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
 #pragma unroll
   for (int i = 0; i < NQ; ++i) {
     const int h = bc.g * a.G + (bc.grp * NQ + i) / WT;
-    bias[i].set(jrow[i] >= 0 ? a.lse[((size_t)bc.b * a.Hq + h) * a.W + jrow[i]] * to_raw : -1000.0f / a.c2, hh);
+    float lse_j = 0.0f;
+    if (jrow[i] >= 0) {
+      // same arithmetic as lse_kernel, which this saves when both passes run in one call
+      if (a.lse_from_part)
+        lse_j = merge_row_partials(
+            a.part + (((size_t)bc.unit * a.n_groups + bc.grp) * (NQ * kTile) + i * kTile + m) * a.n_chunks, a.n_chunks);
+      else lse_j = a.lse[((size_t)bc.b * a.Hq + h) * a.W + jrow[i]];
+    }
+    bias[i].set(jrow[i] >= 0 ? lse_j * to_raw : -1000.0f / a.c2, hh);
   }
   const chunk_t ones = Bias<DT>::ones(hh);
   // Descriptor over scores[b]: Hq * T floats (the host checks that this stays below 2 GiB). Lanes with
@@ -1015,8 +1028,16 @@ static void launch_rowstats(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 
     hipLaunchKernelGGL((rowstats_lds_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
   else
     hipLaunchKernelGGL((rowstats_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
+  if (a.lse_from_part) return;  // the second pass of the same call merges the partials itself
   const int rows = s.Bz * s.Hkv * s.n_groups * NQ * kTile;
   hipLaunchKernelGGL(lse_kernel<NQ>, dim3((rows + 255) / 256), dim3(256), 0, stream, a, rows);
+}
+
+// Whether launch_colsum takes the LDS-staged kernel (the one that can merge the row partials itself).
+template <int DT, int NQ>
+static bool colsum_is_staged(const Shape &s) {
+  if (DT != CKV_BF16) return false;
+  return s.WT == 1 || (NQ % 2 == 0 && s.WT == 2) || (NQ == 3 && s.WT == 3) || (NQ == 4 && s.WT == 4);
 }
 
 template <int DT, int DH, int NQ>
@@ -1103,6 +1124,7 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, b
   const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
 #define CKV_LAUNCH_NQ(NQ)                                                        \
   case NQ:                                                                       \
+    a.lse_from_part = need_lse && need_scores && colsum_is_staged<DT, NQ>(s);    \
     if (need_lse) launch_rowstats<DT, DH, NQ>(s, a, grid, block, stream);        \
     if (need_scores) launch_colsum<DT, DH, NQ>(s, a, grid, block, stream);       \
     break;

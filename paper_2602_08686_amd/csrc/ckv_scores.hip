@@ -26,6 +26,7 @@ hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Works
   a.lse_out = lse_out ? lse_out : (float *)(ws + w.lse_off);
   a.lse = lse_in ? lse_in : a.lse_out;
   a.scores = scores;
+  a.lse_from_part = 0;
   a.group_sum = (p->flags & CKV_FLAG_GROUP_MASS) && !fuse ? 1 : 0;
   a.w_row = fuse ? fuse->w_row : nullptr;
   a.utility = fuse ? fuse->utility : nullptr;
