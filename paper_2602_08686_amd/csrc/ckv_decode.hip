@@ -59,9 +59,9 @@ struct Piece<CKV_F32> {
 // exp2(a - b) with the conventions of an online softmax: a = -inf gives 0 also when b was reset to 0
 __device__ __forceinline__ float exp2_diff(float a, float b) { return exp2f(a - b); }
 
-// NW waves per workgroup, U row steps whose loads are in flight together. With one chunk per
+// NW waves per workgroup, U row steps whose loads are in flight together (PIPE: of the next block too). With one chunk per
 // (unit, query) the workgroup writes the final result itself and no merge kernel follows.
-template <int DT, int DH, int RQ, int NW, int U>
+template <int DT, int DH, int RQ, int NW, int U, bool PIPE>
 __global__ void __launch_bounds__(NW *kWave) decode_partial_kernel(DecodeArgs a) {
   constexpr int E = Piece<DT>::E;
   constexpr int ESIZE = 16 / E;
@@ -111,8 +111,9 @@ __global__ void __launch_bounds__(NW *kWave) decode_partial_kernel(DecodeArgs a)
   const char *kb = static_cast<const char *>(a.k) + ((size_t)b * a.ks[0] + (size_t)g * a.ks[1]) * ESIZE;
   const char *vb = static_cast<const char *>(a.v) + ((size_t)b * a.vs[0] + (size_t)g * a.vs[1]) * ESIZE;
   // a wave takes KPW * U consecutive rows at a time; the workgroup's waves interleave such blocks
-  for (int base = r0 + wave * KPW * U; base < r1; base += NW * KPW * U) {
-    uint4 kraw[U], vraw[U];
+  // The loads of the wave's next block are issued before the current block is worked on: a short KV set
+  // is a handful of dependent round trips otherwise.
+  auto load_block = [&](int base, uint4 (&kraw)[U], uint4 (&vraw)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int row = base + u * KPW + slot;
@@ -123,6 +124,13 @@ __global__ void __launch_bounds__(NW *kWave) decode_partial_kernel(DecodeArgs a)
         vraw[u] = load_piece<STREAM>(vb + ((size_t)row * a.vs[2] + sub * E) * ESIZE);
       }
     }
+  };
+  uint4 kraw[U], vraw[U];
+  const int base0 = r0 + wave * KPW * U;
+  if (base0 < r1) load_block(base0, kraw, vraw);
+  for (int base = base0; base < r1; base += NW * KPW * U) {
+    uint4 knext[U], vnext[U];
+    if (PIPE) load_block(base + NW * KPW * U, knext, vnext);  // rows at and beyond r1 are not read
     float s[U][RQ], vf[U][E];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -158,6 +166,15 @@ __global__ void __launch_bounds__(NW *kWave) decode_partial_kernel(DecodeArgs a)
         for (int e = 0; e < E; ++e) acc[r][e] = fmaf(p, vf[u][e], acc[r][e]);
       }
       m[r] = m_new;
+    }
+    if (PIPE) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        kraw[u] = knext[u];
+        vraw[u] = vnext[u];
+      }
+    } else if (base + NW * KPW * U < r1) {
+      load_block(base + NW * KPW * U, kraw, vraw);
     }
   }
 
@@ -298,8 +315,8 @@ DecodePlan plan_decode(const Shape &s, int n_q, int n_rows) {
   p.grid_y = (int64_t)s.Bz * s.Hkv * n_q * p.head_chunks;
   // Short KV sets (a compact cache): one large workgroup per (unit, query, pair of heads) finishes the job
   // in one launch -- a decoding step is a chain of dependent layers, so a second launch costs more than
-  // reading the few rows once per pair of heads (the second read hits the cache), and two heads per
-  // workgroup leave registers for sixteen waves with four row steps in flight each.
+  // reading the few rows once per pair of heads, and two heads per workgroup leave registers for sixteen
+  // waves with the loads of two blocks of rows in flight each.
   if (n_rows <= 4096 || (p.grid_y >= 1024 && n_rows <= 16384)) {
     p.rq = s.G >= 2 ? 2 : 1;
     p.head_chunks = (s.G + p.rq - 1) / p.rq;
@@ -328,11 +345,11 @@ template <int DT, int DH, int RQ>
 static void launch_decode_t(const DecodeArgs &a, const DecodePlan &p, hipStream_t stream) {
   if (p.n_chunks == 1) {
     if constexpr (RQ <= 2)
-      hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ, 16, 4>), dim3(1, (unsigned)p.grid_y), dim3(16 * kWave), 0,
-                         stream, a);
+      hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ, 16, 2, true>), dim3(1, (unsigned)p.grid_y),
+                         dim3(16 * kWave), 0, stream, a);
     return;
   }
-  hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ, kDecodeWaves, 4>), dim3(p.n_chunks, (unsigned)p.grid_y),
+  hipLaunchKernelGGL((decode_partial_kernel<DT, DH, RQ, kDecodeWaves, 4, false>), dim3(p.n_chunks, (unsigned)p.grid_y),
                      dim3(kDecodeThreads), 0, stream, a);
   hipLaunchKernelGGL((decode_merge_kernel<DH, RQ>), dim3((unsigned)p.grid_y), dim3(kDecodeThreads), 0, stream, a);
 }
