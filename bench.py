@@ -295,7 +295,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
-              "(every (layer, batch, KV head) unit is independent, see DESIGN.md on sharding).", file=sys.stderr)
+              "(every (layer, batch, KV head) unit is independent, so the path would shard over heads or "
+              "batch without any exchange).", file=sys.stderr)
         return 2
 
     import torch
