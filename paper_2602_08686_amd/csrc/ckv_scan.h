@@ -951,12 +951,13 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
     wgt[h] = UTIL && head < a.Hq ? a.w_row[head] : 0.0f;
   }
   float *stage = s_stage[wr.wave];
+  const int n_piped = wr.n_full / kRing * kRing;
+  // (distinct offsets, all outside the descriptor: identical stores could be merged into one)
 #pragma unroll
-  for (int i = 0; i < N_STORES; ++i) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc, 0x80000000u, 0, 0);
+  for (int i = 0; i < N_STORES; ++i) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc, 0x80000000u + 64u * i, 0, 0);
 
   chunk_t kreg[2][NCH];
   f32x16 acc[2];
-  const int n_piped = wr.n_full / kRing * kRing;
   if (n_piped > 0) {
     wait_vm<(kRing - 2) * G::NDMA>();
     read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
