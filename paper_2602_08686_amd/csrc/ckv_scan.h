@@ -377,6 +377,13 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
 constexpr int kRing = 4;  // tile images per wave
+// Cache policy of the pipeline's output stores (column sums, group sums, utilities): sc1. The outputs
+// are consumed by a later kernel, never by this one; with the default policy the stores, although a
+// few percent of the pass's bytes, cost it 6-8 us more (measured on the 32k / batch-16 shape).
+#ifndef CKV_OUT_STORE_AUX
+#define CKV_OUT_STORE_AUX 16
+#endif
+constexpr int kOutStoreAux = CKV_OUT_STORE_AUX;
 
 template <int DT, int DH>
 struct Geom {
@@ -755,7 +762,7 @@ __device__ __forceinline__ void flush_column_sums(const ScoreArgs &a, const Bloc
     const f32x4 v = *reinterpret_cast<const f32x4 *>(stage + (valid ? mine : 0) * (kRing * kTile) + key4);
     const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + t_first + key4) * 4) : 0x80000000u;
     typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, kOutStoreAux);
   }
 }
 
@@ -778,7 +785,7 @@ __device__ __forceinline__ void flush_group_sums(const ScoreArgs &a, const Block
   for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], 32);
   const uint32_t off = half == 0 ? (uint32_t)((bc.g * a.T + t_first + key4) * 4) : 0x80000000u;
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, acc), rsrc_g, off, 0, 0);
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, acc), rsrc_g, off, 0, kOutStoreAux);
 }
 
 // Fused form of the flush (ckv_window_utility): instead of the column sums, the wave writes the
@@ -852,7 +859,7 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
                        ((first_block && key4 < kUtilHead) || (last_block && key4 >= BLK - kUtilCarry));
     const f32x4 v = *reinterpret_cast<const f32x4 *>(rows + (mine < NH ? mine : 0) * kUtilRow + kUtilCarry + key4);
     const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + t_first + key4) * 4) : 0x80000000u;
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, kOutStoreAux);
   }
   float best[4];
   if (a.pool == CKV_POOL_MAX) {
@@ -882,7 +889,7 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
   const bool emit = grp >= kUtilShift / 4 + 1 || !first_block;
   const uint32_t off_u =
       emit ? (uint32_t)((bc.g * a.P + t_first - kUtilShift + 4 * grp + 2 * (lane >> 5)) * 4) : 0x80000000u;
-  __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, out), rsrc_u, off_u, 0, 0);
+  __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, out), rsrc_u, off_u, 0, kOutStoreAux);
   // carry: the block's last kUtilCarry values move in front of the rows for the next block
   constexpr int PER = kUtilCarry / 4;  // 128-bit pieces per head
   static_assert(PER * NH <= kWave, "one piece per lane");
