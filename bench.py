@@ -270,8 +270,8 @@ def decode_bench(args, w, n_layers, torch, B, wl) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c3",
                     choices=["c1", "c2", "c3", "c4", "c5", "s16k_b256", "s32k_b512", "s64k_b1024", "s128k_b2048", "s32k_b128"],
                     help="c3 is the workload the metric is quoted on; s*: length scaling at a fixed retained ratio "
@@ -353,7 +353,7 @@ def main() -> int:
     value = layer_bytes / (ms_per_layer * 1e-3) / 1e9
 
     # Per-kernel timing of the two scan passes with events on the launch stream (torch's current one).
-    reps = max(2, args.steps)
+    reps = max(2, min(args.steps, 5))
     ev = lambda: torch.cuda.Event(enable_timing=True)
     lse_buf = torch.empty(w.batch, w.n_q_heads, w.window, device=dev)
     pairs1, pairs2 = [], []
