@@ -6,6 +6,12 @@
  *
  *   ckv_window_scores -> ckv_apply_tables -> ckv_select_topk -> ckv_compact_kv
  *
+ * Further entry points, each documented where it is declared: ckv_window_lse (the scan's first half),
+ * ckv_window_utility (the first two calls as one, without the per-head masses in memory), the calls of
+ * the paper's layer-shared mode (ckv_alpha_accumulate, ckv_risk_struct, ckv_shared_utility,
+ * ckv_compact_kv_shared) and a decode-side consumer of the compact cache (ckv_decode_attention,
+ * ckv_discarded_mass).
+ *
  * Notation (paper Sec. 3-4): T = prompt length (keys/values cached at the end of prefill, the
  * observation window included), W = |Omega| = observation window (the last W query positions),
  * P = T - W = prefix length that competes for the budget, Hq / Hkv = query / key-value heads,
