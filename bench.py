@@ -374,6 +374,21 @@ def main() -> int:
             c.record()
             pairs1.append((a, b_))
             pairs2.append((b_, c))
+    # Spread of one layer's whole call sequence (events around each layer of two more steps).
+    per_layer = []
+    for _ in range(2):
+        marks = [ev() for _ in range(n_layers + 1)]
+        marks[0].record()
+        for l in range(n_layers):
+            t = layers[l]
+            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, buf, lse=None if lse is None else lse[l],
+                              fused_utility=not args.unfused)
+            marks[l + 1].record()
+        torch.cuda.synchronize()
+        per_layer += [marks[l].elapsed_time(marks[l + 1]) for l in range(n_layers)]
+    per_layer.sort()
+    pct = lambda f: round(per_layer[min(len(per_layer) - 1, int(f * len(per_layer)))], 4)
+    layer_ms = {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "samples": len(per_layer)}
     pairs3, pairs4 = [], []
     for _ in range(reps):
         for l in range(n_layers):
@@ -431,6 +446,7 @@ def main() -> int:
                         "colsum": round(scan_flops(w) / (ms_pass2 * 1e-3) / 1e12, 1),  # fused: its fix-up kernel included
                         "peak": MFMA_BF16_PEAK_TFLOPS},
         "whole_pass_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "layer_ms": layer_ms,
     }
 
     if args.copy_calibration:
