@@ -284,6 +284,24 @@ def layer_shared_layer(alpha, k_bits, v_bits, v, *, W, B_layer, cap, w_head_row,
                 k_out=gather_shared(k_bits, idx, count), v_out=gather_shared(v_bits, idx, count))
 
 
+def map_table_depth(table, n_layers_dst):
+    """Rows of a table compiled on L_src layers ([L_src, ...]) -> [L_dst, ...] for a model of another depth
+    (App. "Model choice and cross-architecture applicability": a monotonic depth mapping, relative-depth
+    interpolation): target layer l sits at relative depth l / (L_dst - 1), i.e. at source coordinate
+    x = l (L_src - 1) / (L_dst - 1), and takes the linear interpolation of the two neighbouring source rows
+    (row 0 for a one-layer target)."""
+    t = np.asarray(table, dtype=np.float64)
+    L_src, L_dst = t.shape[0], int(n_layers_dst)
+    out = np.empty((L_dst,) + t.shape[1:], dtype=np.float64)
+    for l in range(L_dst):
+        x = 0.0 if L_dst == 1 else l * (L_src - 1) / (L_dst - 1)
+        i = min(int(np.floor(x)), L_src - 1)
+        j = min(i + 1, L_src - 1)
+        f = x - i
+        out[l] = (1.0 - f) * t[i] + f * t[j]
+    return out
+
+
 # ---------------------------------------------------------------------------------------------------
 # Decode-side consumer (Proposition 1 and its proof in App. A): a decoding query attends over the
 # retained set only; the discarded mass m_t of its full attention row measures what compression lost.

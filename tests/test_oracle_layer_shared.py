@@ -100,3 +100,25 @@ def test_gather_shared_and_whole_layer():
     r = oracle.layer_shared_layer(alpha, k, v, v, W=W, B_layer=20, cap=20, w_head_row=w, gate_layer=gate,
                                   risk_bins=[(0, 0), (2, 1)])
     assert (r["count"] == W).all()
+
+
+def test_depth_mapping_is_relative_depth_interpolation():
+    rng = np.random.default_rng(5)
+    t = rng.random((32, 6))
+    np.testing.assert_allclose(oracle.map_table_depth(t, 32), t, rtol=1e-15)                   # same depth: identity
+    for L in (28, 40, 80, 2):
+        m = oracle.map_table_depth(t, L)
+        np.testing.assert_allclose(m[0], t[0], rtol=1e-15)                                     # first and last layer
+        np.testing.assert_allclose(m[-1], t[-1], rtol=1e-12)
+        x = np.arange(L) * 31 / (L - 1)
+        for c in range(6):                                                                     # library interpolation
+            np.testing.assert_allclose(m[:, c], np.interp(x, np.arange(32), t[:, c]), rtol=1e-12, atol=1e-15)
+    ramp = np.arange(32, dtype=np.float64)[:, None] * np.array([[1.0, -2.0]]) + 3.0
+    np.testing.assert_allclose(oracle.map_table_depth(ramp, 28)[:, 0], 3.0 + np.arange(28) * 31 / 27, rtol=1e-13)  # linear tables map exactly
+    mono = np.sort(rng.random((32, 3)), axis=0)
+    assert (np.diff(oracle.map_table_depth(mono, 48), axis=0) >= -1e-15).all()                 # monotone in depth
+    assert oracle.map_table_depth(t, 1).shape == (1, 6)
+    np.testing.assert_array_equal(oracle.map_table_depth(t, 1)[0], t[0])
+    g = rng.random((32, 20, 4))                                                                # gate table: trailing axes ride along
+    np.testing.assert_allclose(oracle.map_table_depth(g, 28)[5], 
+                               (1 - (5 * 31 / 27 - 5)) * g[5] + (5 * 31 / 27 - 5) * g[6], rtol=1e-12)
