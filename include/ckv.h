@@ -9,7 +9,7 @@
  * Further entry points, each documented where it is declared: ckv_window_lse (the scan's first half),
  * ckv_window_utility (the first two calls as one, without the per-head masses in memory), the calls of
  * the paper's layer-shared mode (ckv_alpha_accumulate, ckv_risk_struct, ckv_shared_utility,
- * ckv_compact_kv_shared) and a decode-side consumer of the compact cache (ckv_decode_attention,
+ * ckv_compact_kv_shared), the depth mapping of compiled tables (ckv_map_table_depth) and a decode-side consumer of the compact cache (ckv_decode_attention,
  * ckv_discarded_mass).
  *
  * Notation (paper Sec. 3-4): T = prompt length (keys/values cached at the end of prefill, the
@@ -292,6 +292,18 @@ ckv_status ckv_shared_utility(const ckv_params *params, const float *alpha, cons
  */
 ckv_status ckv_compact_kv_shared(const ckv_params *params, const void *k, const void *v, const int32_t *idx,
                                  const int32_t *count, void *k_out, void *v_out, void *hip_stream);
+
+/*
+ * Depth mapping of a compiled table (paper App. "Model choice and cross-architecture applicability": tables
+ * are compiled on a 32-layer backbone; models of another depth use a monotonic depth mapping, relative-
+ * depth interpolation). mapped[l,:] is the linear interpolation of the two rows of `table` next to the
+ * source coordinate x = l * (n_layers_src - 1) / (n_layers_dst - 1) (row 0 for n_layers_dst = 1). Works
+ * for w_head ([L,Hq]: row_elems = Hq), head_share ([L,Hkv]) and t_gate ([L,n_ent,n_ppl]: row_elems =
+ * n_ent * n_ppl). Table preparation, run once per model.
+ *   table  in  [n_layers_src,row_elems] fp32      mapped  out  [n_layers_dst,row_elems] fp32
+ */
+ckv_status ckv_map_table_depth(const float *table, int32_t n_layers_src, int32_t row_elems, float *mapped,
+                               int32_t n_layers_dst, void *hip_stream);
 
 /*
  * Decode-side consumer of the compact cache (paper Sec. 4.5, Proposition 1; proof in App. A).

@@ -24,7 +24,8 @@ FLAG_GROUP_MASS = 8         # ckv_window_scores writes per-KV-head sums [Bz,Hkv,
 
 EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_alpha_accumulate", "ckv_risk_struct", "ckv_shared_utility", "ckv_compact_kv_shared",
-           "ckv_decode_workspace_bytes", "ckv_decode_attention", "ckv_discarded_mass", "ckv_status_string")
+           "ckv_decode_workspace_bytes", "ckv_decode_attention", "ckv_discarded_mass", "ckv_map_table_depth",
+           "ckv_status_string")
 
 
 class CkvParams(ctypes.Structure):
@@ -89,6 +90,8 @@ def load(path: Optional[Path] = None):
     lib.ckv_decode_attention.restype = ctypes.c_int
     lib.ckv_discarded_mass.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.ckv_discarded_mass.restype = ctypes.c_int
+    lib.ckv_map_table_depth.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_int32, vp]
+    lib.ckv_map_table_depth.restype = ctypes.c_int
     lib.ckv_status_string.argtypes = [ctypes.c_int]
     lib.ckv_status_string.restype = ctypes.c_char_p
     if path is None:
@@ -221,6 +224,13 @@ def ckv_shared_utility(params, alpha, vnorm_ratio, w_head, t_gate, n_ent, n_ppl,
 def ckv_compact_kv_shared(params, k, v, idx, count, k_out, v_out, stream=None):
     _check(load().ckv_compact_kv_shared(ctypes.byref(params), _ptr(k), _ptr(v), _ptr(idx), _ptr(count),
                                         _ptr(k_out), _ptr(v_out), _stream(stream)), "ckv_compact_kv_shared")
+
+
+def ckv_map_table_depth(table, mapped, stream=None):
+    """table [L_src, ...] fp32 -> mapped [L_dst, ...] fp32 (same trailing shape), both contiguous."""
+    row = table[0].numel()
+    _check(load().ckv_map_table_depth(_ptr(table), int(table.shape[0]), int(row), _ptr(mapped), int(mapped.shape[0]),
+                                      _stream(stream)), "ckv_map_table_depth")
 
 
 def ckv_decode_workspace_bytes(params, n_q, n_rows) -> int:

@@ -355,6 +355,15 @@ extern "C" ckv_status ckv_compact_kv_shared(const ckv_params *params, const void
   return CKV_OK;
 }
 
+extern "C" ckv_status ckv_map_table_depth(const float *table, int32_t n_layers_src, int32_t row_elems, float *mapped,
+                                          int32_t n_layers_dst, void *hip_stream) {
+  if (!table || !mapped || n_layers_src < 1 || n_layers_dst < 1 || row_elems < 1) return CKV_EINVAL;
+  if ((int64_t)n_layers_dst * row_elems > (1 << 30)) return CKV_EUNSUPPORTED;
+  if (launch_map_depth(table, n_layers_src, row_elems, mapped, n_layers_dst, (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
 static ckv_status decode_args_ok(const ckv_params *p, int32_t n_q, int32_t n_rows, const int64_t *k_stride,
                                  const int64_t *v_stride) {
   if (n_q < 1 || n_rows < 1 || !k_stride || !v_stride) return CKV_EINVAL;

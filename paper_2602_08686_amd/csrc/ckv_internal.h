@@ -134,6 +134,7 @@ hipError_t launch_shared_utility(const ckv_params *p, const Shape &s, const floa
                                  const float *w_head, const float *t_gate, int n_ent, int n_ppl,
                                  const int32_t *risk_bins, float *utility, float *tau, hipStream_t stream);
 
+hipError_t launch_map_depth(const float *src, int n_src, int row, float *dst, int n_dst, hipStream_t stream);
 // decode-side consumer (Proposition 1): attention over a ragged KV set, discarded mass
 struct DecodePlan {
   int rq;              // query heads of a group that share one sweep over the rows (1, 2, 4 or 8)

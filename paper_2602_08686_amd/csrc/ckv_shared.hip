@@ -169,4 +169,38 @@ hipError_t launch_shared_utility(const ckv_params *p, const Shape &s, const floa
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Depth mapping of a compiled table (paper App., "Model choice and cross-architecture applicability"):
+// relative-depth linear interpolation of the rows of a table compiled on n_src layers to n_dst layers.
+// Table preparation, not part of the per-layer path: one thread per output element.
+// ---------------------------------------------------------------------------------------------
+struct DepthArgs {
+  const float *src;  // [n_src][row]
+  float *dst;        // [n_dst][row]
+  int n_src, n_dst, row;
+};
+
+__global__ void __launch_bounds__(256) map_depth_kernel(DepthArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.n_dst * a.row) return;
+  const int l = i / a.row, c = i % a.row;
+  // x = l (n_src - 1) / (n_dst - 1) in double: the row index and the weight are exact for the table sizes in use
+  const double x = a.n_dst == 1 ? 0.0 : (double)l * (double)(a.n_src - 1) / (double)(a.n_dst - 1);
+  const int lo = min((int)floor(x), a.n_src - 1), hi = min(lo + 1, a.n_src - 1);
+  const double f = x - (double)lo;
+  a.dst[i] = (float)((1.0 - f) * (double)a.src[(size_t)lo * a.row + c] + f * (double)a.src[(size_t)hi * a.row + c]);
+}
+
+hipError_t launch_map_depth(const float *src, int n_src, int row, float *dst, int n_dst, hipStream_t stream) {
+  DepthArgs a;
+  a.src = src;
+  a.dst = dst;
+  a.n_src = n_src;
+  a.n_dst = n_dst;
+  a.row = row;
+  const int n = n_dst * row;
+  hipLaunchKernelGGL(map_depth_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
 }  // namespace ckv

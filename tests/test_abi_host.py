@@ -214,6 +214,16 @@ def test_group_mass_flag_is_validated_on_the_host():
         assert lib.ckv_window_scores(ref(q), d, d, None, None, d, None, d, n, None) == B.CKV_EUNSUPPORTED
 
 
+def test_depth_mapping_is_validated_on_the_host():
+    lib = B.load()
+    d = ctypes.c_void_p(256)
+    assert lib.ckv_map_table_depth(None, 32, 8, d, 28, None) == B.CKV_EINVAL
+    assert lib.ckv_map_table_depth(d, 32, 8, None, 28, None) == B.CKV_EINVAL
+    for bad in ((0, 8, 28), (32, 0, 28), (32, 8, 0)):
+        assert lib.ckv_map_table_depth(d, bad[0], bad[1], d, bad[2], None) == B.CKV_EINVAL
+    assert lib.ckv_map_table_depth(d, 32, 1 << 20, d, 1 << 12, None) == B.CKV_EUNSUPPORTED
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         B.load(tmp_path / "libckv.so")

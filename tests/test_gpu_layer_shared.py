@@ -192,3 +192,20 @@ def test_group_mass_scan_equals_the_sum_over_the_group_heads(w):
     ref_alpha = oracle.alpha_mean(ref_maps)
     assert_scores_close(alpha_g.cpu().numpy(), ref_alpha, "alpha from group masses")
     np.testing.assert_allclose(alpha_g.cpu().numpy(), alpha_h.cpu().numpy(), rtol=2e-6, atol=0)
+
+
+def test_depth_mapping_of_compiled_tables():
+    """A 32-layer head table and gate table mapped to 28, 40 and 1 layers: equal to the oracle within fp32
+    rounding; the same depth is a copy."""
+    g = torch.Generator().manual_seed(11)
+    w_head = torch.empty(32, 28).uniform_(0.5, 1.5, generator=g).to(DEV)
+    gate = (0.8 + 0.01 * torch.randint(0, 21, (32, 20, 4), generator=g).float()).to(DEV)
+    for table in (w_head, gate):
+        for L in (28, 40, 1, 32):
+            mapped = torch.full((L,) + tuple(table.shape[1:]), float("nan"), device=DEV)
+            B.ckv_map_table_depth(table, mapped)
+            torch.cuda.synchronize()
+            ref = oracle.map_table_depth(table.cpu().numpy(), L)
+            np.testing.assert_allclose(mapped.cpu().numpy(), ref, rtol=2e-7, atol=0)
+            if L == 32:
+                assert torch.equal(mapped, table)
