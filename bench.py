@@ -279,8 +279,6 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffers (0 = the config's depth)")
     ap.add_argument("--value-norm", action="store_true")
     ap.add_argument("--given-lse", action="store_true", help="caller-supplied LSE: single pass over K")
-    ap.add_argument("--scan", default="two_kernels", choices=["two_kernels", "single_read"],
-                    help="which implementation of the scan ckv_window_scores uses when it computes LSE itself")
     ap.add_argument("--unfused", action="store_true",
                     help="ckv_window_scores + ckv_apply_tables instead of ckv_window_utility (materialises the "
                          "per-head window mass)")
@@ -313,7 +311,6 @@ def main() -> int:
     w = ({c.name[:2]: c for c in wl.CONFIGS} | {c.name.split("_gqa")[0]: c for c in wl.SWEEP})[args.config]
     n_layers = args.layers or w.n_layers
     flags = B.FLAG_VALUE_NORM if args.value_norm else 0
-    flags |= B.FLAG_SCAN_SINGLE_READ if args.scan == "single_read" else B.FLAG_SCAN_TWO_KERNELS
 
     if args.mode == "layer_shared":
         return layer_shared_bench(args, w, n_layers, torch, B, wl)
@@ -414,21 +411,6 @@ def main() -> int:
     pass2_has_v = args.value_norm and not args.unfused  # the fused call also reads V for the value norms
     scan_ms = {"rowstats+lse": round(ms_pass1, 4),
                ("colsum" if args.unfused else "colsum+tables+vnorm" if pass2_has_v else "colsum+tables"): round(ms_pass2, 4)}
-    if args.scan == "single_read" and not args.given_lse:
-        # the persistent kernel does both passes in one launch: time the call as a whole
-        whole = []
-        for _ in range(reps):
-            for l in range(n_layers):
-                t = layers[l]
-                a, b_ = ev(), ev()
-                a.record()
-                B.ckv_window_scores(params[l], t["q"], t["k"], None, None, buf.scores, None, buf.workspace)
-                b_.record()
-                whole.append((a, b_))
-        torch.cuda.synchronize()
-        dom_ms = sum(a.elapsed_time(b_) for a, b_ in whole) / len(whole)
-        dominant = "fused_scan_kernel"
-        scan_ms["single_read"] = round(dom_ms, 4)
     dom_bytes = scan_bytes(w)
     if pass2_has_v and dominant.startswith("colsum"):
         dominant += " + vnorm_rows_kernel"   # timed together: K and V are each read once in that region
@@ -466,7 +448,7 @@ def main() -> int:
         "config": {"workload": w.name, "layers_per_step": n_layers, "batch": w.batch, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.seq_len, "window": w.window,
                    "budget_per_kv_head": w.budget, "pool": ["none", "avg", "max"][w.pool] + str(w.pool_kernel),
-                   "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed", "scan": args.scan,
+                   "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed",
                    "calls": ("window_scores+apply_tables" if args.unfused else "window_utility") + "+select_topk+compact_kv",
                    "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
         "roofline": roofline,

@@ -54,18 +54,10 @@ typedef enum { CKV_POOL_NONE = 0, CKV_POOL_AVG = 1, CKV_POOL_MAX = 2 } ckv_pool;
 /* flags */
 enum {
   CKV_FLAG_VALUE_NORM = 1u, /* multiply the window mass by the value-norm ratio rho (paper Eq. 4)  */
-  /* ckv_window_scores with lse == NULL has two implementations of the same scan (identical
-   * definitions, results equal within rounding): two kernels that stream K twice (the default), and
-   * one persistent kernel that reads K once and keeps a unit's keys on chip between the passes
-   * (bf16, G*ceil(W/32) <= 4, W <= 64; cooperative launch). SINGLE_READ asks for the latter and is
-   * ignored where it does not exist; TWO_KERNELS names the default explicitly. At most one may be
-   * set.                                                                                            */
-  CKV_FLAG_SCAN_TWO_KERNELS = 2u,
-  CKV_FLAG_SCAN_SINGLE_READ = 4u,
   /* Layer-shared mode only (paper Eq. 4: alpha is a mean over heads): ckv_window_scores writes, instead
    * of every query head's mass, the SUM over the query heads of each KV head, scores [Bz,Hkv,T], and
    * ckv_alpha_accumulate reads that layout -- a quarter of the bytes for groups of four. Exists for
-   * bf16 with W <= 32 and G <= 4 (CKV_EUNSUPPORTED otherwise); excludes SCAN_SINGLE_READ; rejected by
+   * bf16 with W <= 32 and G <= 4 (CKV_EUNSUPPORTED otherwise); rejected by
    * the calls that need per-head masses (ckv_apply_tables, ckv_window_utility).                      */
   CKV_FLAG_GROUP_MASS = 8u
 };
@@ -124,17 +116,6 @@ size_t ckv_workspace_bytes(const ckv_params *params);
 ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const void *k,
                              const void *v, const float *lse, float *scores, float *vnorm_ratio,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
-
-/*
- * Error word of the single-read scan. That scan (see CKV_FLAG_SCAN_SINGLE_READ) is one persistent
- * kernel whose workgroups wait for each other; every such wait is bounded, and a wait that expires
- * (which needs a GPU that cannot keep the whole launch resident) writes a non-zero uint32 at this
- * byte offset of `workspace` -- the scores of that call are then invalid; otherwise that call leaves
- * the word zero. Calls that use the two-kernel scan do not touch it. A caller that wants to check
- * reads it once the stream has reached the call. Returns (size_t)-1 if `params` is invalid or that scan does not
- * exist for the shape (then there is nothing to check).
- */
-size_t ckv_scan_status_offset(const ckv_params *params);
 
 /*
  * First half of the scan on its own: LSE_j of every window row, as defined above (the softmax
@@ -238,7 +219,6 @@ ckv_status ckv_select_topk(const ckv_params *params, const float *utility, const
 ckv_status ckv_compact_kv(const ckv_params *params, const void *k, const void *v, const int32_t *idx,
                           const int32_t *count, void *k_out, void *v_out, void *hip_stream);
 
-/* Static text for a status code; never NULL. */
 /*
  * Layer-shared mode: the paper's Alg. 1 as printed, where ONE window mass alpha serves every layer and
  * head and every layer keeps ONE index set for all its heads. Order of calls for a prompt:
@@ -285,8 +265,8 @@ ckv_status ckv_shared_utility(const ckv_params *params, const float *alpha, cons
                               const int32_t *risk_bins, float *utility, float *tau, void *hip_stream);
 
 /*
- * Gather with one index set per batch element, shared by all KV heads of the layer (paper Alg. 1
- * Gather_tok: "S^(l) is shared across heads within layer l"): for r < count[b], every g
+ * Gather with one index set per batch element, shared by all KV heads of the layer (paper Alg. 1,
+ * Gather_tok: one index set per layer serves every head): for r < count[b], every g
  *     k_out[b,g,r,:] = k[b,g,idx[b,r],:]    v_out[b,g,r,:] = v[b,g,idx[b,r],:]     (bit copies)
  *   idx  in  [Bz,cap] int32      count  in  [Bz] int32      k_out, v_out  out  [Bz,Hkv,cap,d]
  */
@@ -343,6 +323,7 @@ ckv_status ckv_decode_attention(const ckv_params *params, const void *q_dec, int
 ckv_status ckv_discarded_mass(const ckv_params *params, int32_t n_q, const float *lse_full, const float *lse_kept,
                               float *mass, float *eps_tail, void *hip_stream);
 
+/* Static text for a status code; never NULL. */
 const char *ckv_status_string(ckv_status status);
 
 #ifdef __cplusplus

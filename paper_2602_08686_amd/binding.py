@@ -18,11 +18,9 @@ CKV_OK, CKV_EINVAL, CKV_EUNSUPPORTED, CKV_EWORKSPACE, CKV_EHIP = range(5)
 CKV_F32, CKV_BF16 = 0, 1
 POOL_NONE, POOL_AVG, POOL_MAX = 0, 1, 2
 FLAG_VALUE_NORM = 1
-FLAG_SCAN_TWO_KERNELS = 2   # force the scan that streams K twice
-FLAG_SCAN_SINGLE_READ = 4   # force the persistent scan that reads K once (where it exists)
 FLAG_GROUP_MASS = 8         # ckv_window_scores writes per-KV-head sums [Bz,Hkv,T] (layer-shared mode)
 
-EXPORTS = ("ckv_workspace_bytes", "ckv_scan_status_offset", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
+EXPORTS = ("ckv_workspace_bytes", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_alpha_accumulate", "ckv_risk_struct", "ckv_shared_utility", "ckv_compact_kv_shared",
            "ckv_decode_workspace_bytes", "ckv_decode_attention", "ckv_discarded_mass", "ckv_map_table_depth",
            "ckv_status_string")
@@ -60,8 +58,6 @@ def load(path: Optional[Path] = None):
     vp, pp = ctypes.c_void_p, ctypes.POINTER(CkvParams)
     lib.ckv_workspace_bytes.argtypes = [pp]
     lib.ckv_workspace_bytes.restype = ctypes.c_size_t
-    lib.ckv_scan_status_offset.argtypes = [pp]
-    lib.ckv_scan_status_offset.restype = ctypes.c_size_t
     lib.ckv_window_scores.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ckv_window_scores.restype = ctypes.c_int
     lib.ckv_window_lse.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -154,12 +150,6 @@ def _check(status: int, where: str):
 
 def ckv_workspace_bytes(params: CkvParams) -> int:
     return int(load().ckv_workspace_bytes(ctypes.byref(params)))
-
-
-def ckv_scan_status_offset(params: CkvParams) -> int:
-    """Byte offset of the single-read scan's error word in the workspace, or -1 where there is none."""
-    off = int(load().ckv_scan_status_offset(ctypes.byref(params)))
-    return -1 if off == ctypes.c_size_t(-1).value else off
 
 
 def ckv_window_scores(params, q_win, k, v, lse, scores, vnorm_ratio, workspace, stream=None):

@@ -21,11 +21,7 @@ ckv_status validate(const ckv_params *p) {
   if (p->pool != CKV_POOL_NONE && (p->pool_kernel < 1 || p->pool_kernel > 63 || p->pool_kernel % 2 == 0))
     return CKV_EINVAL;
   if (p->budget_per_kv_head < p->window) return CKV_EINVAL;
-  if (p->flags & ~(uint32_t)(CKV_FLAG_VALUE_NORM | CKV_FLAG_SCAN_TWO_KERNELS | CKV_FLAG_SCAN_SINGLE_READ |
-                             CKV_FLAG_GROUP_MASS))
-    return CKV_EINVAL;
-  if ((p->flags & CKV_FLAG_SCAN_TWO_KERNELS) && (p->flags & CKV_FLAG_SCAN_SINGLE_READ)) return CKV_EINVAL;
-  if ((p->flags & CKV_FLAG_GROUP_MASS) && (p->flags & CKV_FLAG_SCAN_SINGLE_READ)) return CKV_EINVAL;
+  if (p->flags & ~(uint32_t)(CKV_FLAG_VALUE_NORM | CKV_FLAG_GROUP_MASS)) return CKV_EINVAL;
   if (p->head_dim < 1) return CKV_EINVAL;
   const int64_t b_tot = (int64_t)p->budget_per_kv_head * p->n_kv_heads;
   int64_t need = b_tot - (int64_t)(p->n_kv_heads - 1) * p->window;
@@ -43,6 +39,8 @@ ckv_status validate(const ckv_params *p) {
   if (p->window > kMaxQTiles * kTile) return CKV_EUNSUPPORTED;
   if ((int64_t)p->batch * p->n_kv_heads > 65535) return CKV_EUNSUPPORTED;  // grid.y
   if (p->seq_len > (1 << 24)) return CKV_EUNSUPPORTED;
+  // the staged scan addresses the 32 rows of a key tile with 32-bit offsets
+  if (p->k_stride[2] * (int64_t)(p->dtype == CKV_BF16 ? 2 : 4) * kTile >= ((int64_t)1 << 31)) return CKV_EUNSUPPORTED;
   if ((int64_t)p->n_q_heads * p->seq_len >= (1 << 29)) return CKV_EUNSUPPORTED;  // scores of one batch element: < 2 GiB
   return CKV_OK;
 }
@@ -82,11 +80,6 @@ void derive(const ckv_params *p, Shape *s) {
   s->keys_per_wave = (int)kpw;
   s->n_chunks = (int)((s->T + kScoreWaves * kpw - 1) / (kScoreWaves * kpw));
   s->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)s->d);
-  // Single-read scan (bf16, one query-tile group, W <= 64): exists beside the two-kernel scan and is used
-  // only on request. Measured on the 32k / batch-16 GQA shape it is the slower of the two (its team
-  // exchanges and its one-wave-per-SIMD pipelines cost more than the second read of K saves).
-  s->fused_ok = p->dtype == CKV_BF16 && s->n_groups == 1 && s->NQ <= kScoreWaves && s->WT <= 2;
-  s->fused = s->fused_ok && (p->flags & CKV_FLAG_SCAN_SINGLE_READ) != 0;
 }
 
 int vnorm_blocks_per_unit(const Shape &s) {
@@ -106,12 +99,6 @@ void layout(const ckv_params *p, const Shape &s, Workspace *w) {
   w->vsum_off = off;
   w->vsum_bytes = (p->flags & CKV_FLAG_VALUE_NORM) ? units * vnorm_blocks_per_unit(s) * sizeof(float) : 0;
   off = align256(off + w->vsum_bytes);
-  w->sync_off = off;
-  w->sync_bytes = s.fused_ok ? kFusedSyncBytes : 0;
-  off = align256(off + w->sync_bytes);
-  w->fpart_off = off;
-  w->fpart_bytes = s.fused_ok ? (size_t)2 * kFusedGridMax * s.NQ * kTile * sizeof(float2) : 0;
-  off = align256(off + w->fpart_bytes);
   w->select_off = off;
   w->select_bytes = select_workspace_bytes(s);
   off = align256(off + w->select_bytes);
@@ -134,15 +121,6 @@ extern "C" size_t ckv_workspace_bytes(const ckv_params *params) {
   derive(params, &s);
   layout(params, s, &w);
   return w.total;
-}
-
-extern "C" size_t ckv_scan_status_offset(const ckv_params *params) {
-  if (validate(params) != CKV_OK) return (size_t)-1;
-  Shape s;
-  Workspace w;
-  derive(params, &s);
-  layout(params, s, &w);
-  return s.fused_ok ? w.sync_off + sizeof(uint32_t) : (size_t)-1;  // sync word 1
 }
 
 extern "C" ckv_status ckv_window_scores(const ckv_params *params, const void *q_win, const void *k,
@@ -247,12 +225,10 @@ extern "C" ckv_status ckv_window_utility(const ckv_params *params, const void *q
     const int kernel = params->pool == CKV_POOL_NONE ? 1 : params->pool_kernel;
     fuse.radius = kernel / 2;
     fuse.inv_kernel = 1.0f / (float)kernel;
-    Shape s2 = s;
-    s2.fused = false;  // the fused pass belongs to the two-kernel scan
-    if (launch_window_scores(params, s2, w, q_win, k, lse, nullptr, scores_scratch, (char *)workspace, stream,
+    if (launch_window_scores(params, s, w, q_win, k, lse, nullptr, scores_scratch, (char *)workspace, stream,
                              &fuse) != hipSuccess)
       return CKV_EHIP;
-    if (launch_utility_fixup(params, s2, scores_scratch, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,
+    if (launch_utility_fixup(params, s, scores_scratch, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,
                              utility, budget, tau, stream) != hipSuccess)
       return CKV_EHIP;
     if (vn && launch_value_norm(params, s, w, v, vnorm_ratio, (char *)workspace, stream, utility) != hipSuccess)

@@ -16,6 +16,22 @@ constexpr int kMaxQTiles = 4;      // query-row tiles a wave keeps in registers
 constexpr int kScoreWaves = 4;     // waves per workgroup in the scan kernels
 constexpr int kComputeUnits = 256; // MI355X
 constexpr int kSelectThreads = 1024;
+// Geometry of the fused utility form of the scan's second pass, shared by that pass (ckv_scan.h) and by
+// the kernel that finishes what it leaves out (ckv_tables.hip). The pass works in rounds of
+// kRing * kTile keys per wave; each round writes the utilities of the kRing * kTile keys that end
+// kUtilShift keys before the round does, keeps its last kUtilCarry column sums in front of the next
+// round's, and stores raw column sums for the first kUtilHead and the last kUtilCarry keys of a wave's
+// pipelined range; the first four keys of a range, its last kUtilShift pipelined keys and its tail tiles
+// are finished by the other kernel.
+constexpr int kRing = 4;           // key-tile images per wave, and tiles per pipeline round
+constexpr int kUtilShift = 32;
+constexpr int kUtilCarry = 40;
+constexpr int kUtilHead = 8;
+constexpr int kUtilMaxRadius = 3;  // pooling kernels of up to 7 taps
+static_assert(kUtilShift % 4 == 0 && kUtilCarry % 4 == 0 && kUtilHead % 4 == 0, "128-bit pieces");
+static_assert(kUtilCarry >= kUtilShift + 4 + kUtilMaxRadius, "a round's first output window reaches this far back");
+static_assert(kUtilHead >= 4 + kUtilMaxRadius, "the range's first four keys need their right neighbours");
+static_assert(kUtilShift >= kUtilMaxRadius, "a round's last output window stays inside the round");
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kValueNormEps = 1e-6f;
@@ -31,8 +47,6 @@ struct Shape {
   int keys_per_wave;
   int n_chunks;     // workgroups along the key axis per (unit, group)
   float scale;      // softmax scale
-  bool fused_ok;    // the single-read scan kernel exists for this shape (bf16, one query-tile group)
-  bool fused;       // ... and is the one ckv_window_scores uses when it computes LSE itself
 };
 
 // A 16-byte piece of a row; STREAM marks data that is used once (non-temporal: it should not displace
@@ -74,22 +88,11 @@ struct Workspace {
   size_t part_off, part_bytes;   // float2 [units][n_tiles*32][n_chunks] row-stat partials
   size_t lse_off, lse_bytes;     // float  [Bz][Hq][W]
   size_t vsum_off, vsum_bytes;   // float  [units][vnorm blocks] partial sums of value norms
-  size_t sync_off, sync_bytes;   // uint32 synchronisation words of the single-read scan
-  size_t fpart_off, fpart_bytes; // float2 [2][workgroups][NQ*32] row partials of the single-read scan
   size_t select_off, select_bytes;  // int: the split selection's merged histograms, slice counts, thresholds
   size_t total;
 };
 void layout(const ckv_params *p, const Shape &s, Workspace *w);
 int vnorm_blocks_per_unit(const Shape &s);
-
-// Where the single-read scan keeps its synchronisation words and row partials, and its grid.
-struct FusedLaunch {
-  uint32_t *sync;
-  float2 *fpart;
-  int grid;
-};
-constexpr int kFusedGridMax = 1024;   // workgroups the partial buffer is sized for
-constexpr int kFusedSyncBytes = 256;
 
 // Kernel launchers (each returns hipGetLastError() after its launches).
 // lse_in == nullptr: pass 1 first, LSE into lse_out (or the workspace). scores == nullptr: pass 1 only.

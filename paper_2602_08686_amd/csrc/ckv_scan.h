@@ -376,7 +376,6 @@ __global__ void __launch_bounds__(kScoreWaves *kWave, 2) colsum_kernel(ScoreArgs
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
-constexpr int kRing = 4;  // tile images per wave
 // Cache policy of the pipeline's output stores (column sums, group sums, utilities): sc1. The outputs
 // are consumed by a later kernel, never by this one; with the default policy the stores, although a
 // few percent of the pass's bytes, cost it 6-8 us more (measured on the 32k / batch-16 shape).
@@ -800,11 +799,7 @@ __device__ __forceinline__ void flush_group_sums(const ScoreArgs &a, const Block
 // four consecutive keys each (three 128-bit reads per head); the halves then swap so that each lane
 // ends up with the group maximum of two adjacent keys and stores them with one 64-bit store. The taps
 // are combined left to right, as the stand-alone tables kernel does.
-constexpr int kUtilShift = 32;    // a flush covers the 128 keys that end this many keys before the block does
-constexpr int kUtilCarry = 40;    // values of the previous block kept in front of a stage row (shift + 8)
-constexpr int kUtilHead = 8;      // raw column sums stored at the front of a range's first block
 constexpr int kUtilRow = kUtilCarry + kRing * kTile;
-constexpr int kUtilMaxRadius = 3; // pooling kernels of up to 7 taps
 template <int NH, int POOL, int R>
 __device__ __forceinline__ void pooled_group_max(const ScoreArgs &a, const float *rows, int lane, int heads_left,
                                                  const float (&wgt)[NH], float (&best)[4]) {
@@ -1023,10 +1018,6 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
   }
 }
 
-}  // namespace ckv
-#include "ckv_scan_fused.h"
-namespace ckv {
-
 // ---------------------------------------------------------------------------------------------
 // Launch
 // ---------------------------------------------------------------------------------------------
@@ -1080,54 +1071,8 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
   hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
 }
 
-// Fused single-read scan (bf16, all query tiles in one wave): one cooperative launch of one workgroup
-// per CU after a tiny kernel that clears the synchronisation words. Returns hipErrorNotSupported when
-// no instantiation fits, so the caller can fall back to the two-kernel scan.
-template <int DT, int DH, int NQ>
-static hipError_t launch_fused(const Shape &s, const ScoreArgs &a, const FusedLaunch &fl, hipStream_t stream) {
-  if constexpr (DT != CKV_BF16) {
-    return hipErrorNotSupported;
-  } else {
-    // query tiles per phase: two for the four-tile groups, else one head
-    const void *kernel = nullptr;
-    if constexpr (NQ == 4) {
-      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 4, 1, 1>;  // 64 more registers for Q would spill
-      if (s.WT == 2) kernel = (const void *)fused_scan_kernel<DT, DH, 4, 2, 2>;
-    } else if constexpr (NQ == 3) {
-      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 3, 1, 1>;
-    } else if constexpr (NQ == 2) {
-      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 2, 1, 1>;
-      if (s.WT == 2) kernel = (const void *)fused_scan_kernel<DT, DH, 2, 2, 2>;
-    } else {
-      if (s.WT == 1) kernel = (const void *)fused_scan_kernel<DT, DH, 1, 1, 1>;
-    }
-    if (!kernel) return hipErrorNotSupported;
-    hipLaunchKernelGGL(fused_init_kernel, dim3(1), dim3(kFusedSyncWords), 0, stream, fl.sync);
-    ScoreArgs ka = a;
-    FusedArgs fa;
-    fa.sync = fl.sync;
-    fa.fpart = fl.fpart;
-    fa.units = s.Bz * s.Hkv;
-    void *params[] = {&ka, &fa};
-    return hipLaunchCooperativeKernel(kernel, dim3(fl.grid), dim3(kScoreWaves * kWave), params, 0, stream);
-  }
-}
-
 template <int DT, int DH>
-static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                  const FusedLaunch *fl, hipStream_t stream) {
-  if (fl && need_lse && need_scores) {
-    hipError_t e = hipErrorNotSupported;
-    switch (s.NQ) {
-      case 1: e = launch_fused<DT, DH, 1>(s, a, *fl, stream); break;
-      case 2: e = launch_fused<DT, DH, 2>(s, a, *fl, stream); break;
-      case 3: e = launch_fused<DT, DH, 3>(s, a, *fl, stream); break;
-      case 4: e = launch_fused<DT, DH, 4>(s, a, *fl, stream); break;
-      default: break;
-    }
-    if (e == hipSuccess) return hipGetLastError();
-    (void)hipGetLastError();  // refused (no instantiation, or the cooperative launch does not fit): two-kernel scan
-  }
+static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream) {
   const int units = s.Bz * s.Hkv;
   const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
 #define CKV_LAUNCH_NQ(NQ)                                                        \
@@ -1150,13 +1095,13 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, b
 
 // One definition per (element type, head size), each in a translation unit of its own.
 hipError_t launch_scores_bf16_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   const FusedLaunch *fl, hipStream_t stream);
+                                   hipStream_t stream);
 hipError_t launch_scores_bf16_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   const FusedLaunch *fl, hipStream_t stream);
+                                   hipStream_t stream);
 hipError_t launch_scores_f32_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   const FusedLaunch *fl, hipStream_t stream);
+                                   hipStream_t stream);
 hipError_t launch_scores_f32_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   const FusedLaunch *fl, hipStream_t stream);
+                                   hipStream_t stream);
 
 }  // namespace ckv
 #endif

@@ -3,7 +3,7 @@
 
 namespace ckv {
 hipError_t launch_scores_f32_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                  const FusedLaunch *fl, hipStream_t stream) {
-  return launch_scores_t<CKV_F32, 128>(s, a, need_lse, need_scores, fl, stream);
+                                  hipStream_t stream) {
+  return launch_scores_t<CKV_F32, 128>(s, a, need_lse, need_scores, stream);
 }
 }  // namespace ckv

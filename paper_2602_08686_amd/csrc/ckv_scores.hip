@@ -34,24 +34,12 @@ hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Works
   a.radius = fuse ? fuse->radius : 0;
   a.inv_kernel = fuse ? fuse->inv_kernel : 1.0f;
   const bool need_lse = lse_in == nullptr, need_scores = scores != nullptr;
-  FusedLaunch fl;
-  const FusedLaunch *use_fused = nullptr;
-  if (s.fused && need_lse && need_scores) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
-      fl.sync = (uint32_t *)(ws + w.sync_off);
-      fl.fpart = (float2 *)(ws + w.fpart_off);
-      fl.grid = cus < kFusedGridMax ? cus : kFusedGridMax;  // one workgroup per CU
-      use_fused = &fl;
-    }
-  }
   if (p->dtype == CKV_BF16) {
-    if (s.d == 128) return launch_scores_bf16_d128(s, a, need_lse, need_scores, use_fused, stream);
-    return launch_scores_bf16_d64(s, a, need_lse, need_scores, use_fused, stream);
+    if (s.d == 128) return launch_scores_bf16_d128(s, a, need_lse, need_scores, stream);
+    return launch_scores_bf16_d64(s, a, need_lse, need_scores, stream);
   }
-  if (s.d == 128) return launch_scores_f32_d128(s, a, need_lse, need_scores, use_fused, stream);
-  return launch_scores_f32_d64(s, a, need_lse, need_scores, use_fused, stream);
+  if (s.d == 128) return launch_scores_f32_d128(s, a, need_lse, need_scores, stream);
+  return launch_scores_f32_d64(s, a, need_lse, need_scores, stream);
 }
 
 // ---------------------------------------------------------------------------------------------

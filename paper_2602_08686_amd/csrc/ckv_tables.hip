@@ -215,8 +215,8 @@ struct FixupArgs {
   int keys_per_wave, n_ranges;  // the scan's split of the key axis
 };
 constexpr int kFixupThreads = 64;
-constexpr int kScanBlockKeys = 128;  // keys per pipeline round of the scan (4 tiles of 32)
-constexpr int kScanTrail = 32;       // pipelined keys at the end of a range that the scan leaves to this kernel
+constexpr int kScanBlockKeys = kRing * kTile;  // keys per pipeline round of the scan
+constexpr int kScanTrail = kUtilShift;         // pipelined keys at the end of a range that the scan leaves to this kernel
 
 template <int POOL, int R>
 __global__ void __launch_bounds__(kFixupThreads) tables_fixup_kernel(TablesArgs a, FixupArgs f) {
@@ -225,8 +225,8 @@ __global__ void __launch_bounds__(kFixupThreads) tables_fixup_kernel(TablesArgs 
   const int t_begin = range * f.keys_per_wave;
   if (t_begin >= a.T) return;
   const int t_end = min(t_begin + f.keys_per_wave, a.T);
-  const int n_full = max(0, (min(t_end, a.P) - t_begin) / 32);   // tiles wholly inside the prefix
-  const int n_blocks = n_full / 4;                               // pipeline rounds
+  const int n_full = max(0, (min(t_end, a.P) - t_begin) / kTile);   // tiles wholly inside the prefix
+  const int n_blocks = n_full / kRing;                               // pipeline rounds
   const int tail0 = t_begin + n_blocks * kScanBlockKeys, tail1 = min(t_end, a.P);
   const int n_tail = tail1 > tail0 ? (tail1 - tail0 + 3) / 4 : 0;
   const int n_edge = n_blocks > 0 ? 1 + kScanTrail / 4 : 0;

@@ -28,11 +28,17 @@ def params_of(w: wl.Workload, q, k, v, layer=0, flags=0, cap=None) -> B.CkvParam
                         cap=w.cap if cap is None else cap, layer=layer, n_layers=w.n_layers, flags=flags)
 
 
-def run_gpu(w: wl.Workload, layer_t: dict, tables: dict, layer=0, flags=0, lse=None):
+def run_gpu(w: wl.Workload, layer_t: dict, tables: dict, layer=0, flags=0, lse=None, fused_utility=False):
+    """fused_utility: ckv_window_utility in place of ckv_window_scores + ckv_apply_tables (what bench.py
+    times); buf.scores is then scratch, prefilled with NaN like buf.utility so that a position the
+    kernels leave unwritten shows up."""
     q, k, v = layer_t["q"], layer_t["k"], layer_t["v"]
     p = params_of(w, q, k, v, layer, flags)
     buf = B.LayerBuffers(p, q.device)
-    B.retention_layer(p, q, k, v, tables, buf, lse=lse)
+    if fused_utility:
+        buf.scores.fill_(float("nan"))
+        buf.utility.fill_(float("nan"))
+    B.retention_layer(p, q, k, v, tables, buf, lse=lse, fused_utility=fused_utility)
     torch.cuda.synchronize()
     return p, buf
 
@@ -74,7 +80,8 @@ def assert_index_sets_match(gpu_idx, gpu_count, ref_idx, ref_count, ref_utility,
             u = ref_utility[b, g].astype(np.float64)
             kp = int(budget[b, g]) - W
             cand = u[u >= tau[b]]
-            bounds = [float(tau[b])]
+            # the gate's threshold is a boundary only where it can exclude something (tau = 0: gate off)
+            bounds = [float(tau[b])] if tau[b] > 0 else []
             if len(cand) > kp > 0:
                 srt = np.sort(cand)[::-1]
                 bounds.append(float(srt[kp - 1]))

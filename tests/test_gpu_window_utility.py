@@ -1,9 +1,14 @@
 """GPU parity of ckv_window_utility (scan + tables in one call, the per-head window mass not
 materialised): against the CPU oracle, and against the two unfused calls on the same tensors.
 
-Shapes are chosen so that the fused second pass has whole 128-key pipeline rounds per wave (block
-interiors come from the scan kernel, block edges and range tails from the fix-up kernel), for every
-pooling mode and radius it takes, and so that the shapes it does not take go through the scratch path."""
+The fused second pass works on 128-key pipeline rounds per wave: the first and the last round of a
+wave's key range treat their edges specially (raw column sums for the fix-up kernel), rounds in between
+only carry the previous round's tail in front. The shapes marked "rounds" give every wave at least
+three rounds (batch x KV heads x T >= 3 * 128 * 1024 keys over the 1024 waves of a launch), so that
+first, middle and last rounds all meet the oracle, for every pooling mode and radius the fused pass
+takes and for both head sizes. wu_short has no whole round at all (range tails and the fix-up kernel
+only). The last group holds shapes the fused pass does not take: they run the two steps through the
+scratch buffer."""
 import numpy as np
 import pytest
 import torch
@@ -23,17 +28,24 @@ def _case(name, dtype, Bz, Hq, Hkv, d, T, W, pool, kernel, budget, **kw):
 
 # (workload, value norm)
 CASES = [
-    (_case("wu_gqa4_avg7", "bf16", 2, 8, 2, 128, 40000, 32, wl.POOL_AVG, 7, 600, shares=True, pareto_frac=0.05), False),
-    (_case("wu_gqa4_max7_ragged", "bf16", 1, 8, 2, 128, 50004, 32, wl.POOL_MAX, 7, 700, needles=5, sink_scale=8.0), False),
-    (_case("wu_mha_avg5_gate", "bf16", 3, 2, 2, 128, 36000, 32, wl.POOL_AVG, 5, 300, gate=True), False),
-    (_case("wu_gqa3_max3", "bf16", 1, 3, 1, 128, 66000, 32, wl.POOL_MAX, 3, 500, head_key_scale=True), False),
-    (_case("wu_gqa2_nopool_w20", "bf16", 2, 4, 2, 128, 30000, 20, wl.POOL_NONE, 1, 400, shares=True), False),
-    (_case("wu_d64_avg7", "bf16", 1, 4, 1, 64, 70000, 32, wl.POOL_AVG, 7, 400), False),
+    # rounds per wave >= 3 (first, middle and last rounds of the fused flush)
+    (_case("wu_gqa4_avg7", "bf16", 4, 8, 2, 128, 49152, 32, wl.POOL_AVG, 7, 600, shares=True, pareto_frac=0.05), False),
+    (_case("wu_gqa4_max7_ragged", "bf16", 4, 8, 2, 128, 50004, 32, wl.POOL_MAX, 7, 700, needles=5, sink_scale=8.0), False),
+    (_case("wu_mha_avg5_gate", "bf16", 6, 2, 2, 128, 36000, 32, wl.POOL_AVG, 5, 300, gate=True), False),
+    (_case("wu_gqa3_max3", "bf16", 3, 6, 2, 128, 66000, 32, wl.POOL_MAX, 3, 500, head_key_scale=True), False),
+    (_case("wu_gqa2_avg3", "bf16", 4, 4, 2, 128, 50000, 32, wl.POOL_AVG, 3, 400, shares=True), False),
+    (_case("wu_gqa4_max5", "bf16", 2, 16, 4, 128, 50000, 32, wl.POOL_MAX, 5, 300), False),
+    (_case("wu_gqa2_nopool_w20", "bf16", 6, 4, 2, 128, 33000, 20, wl.POOL_NONE, 1, 400, shares=True), False),
+    (_case("wu_d64_avg7", "bf16", 2, 16, 4, 64, 70000, 32, wl.POOL_AVG, 7, 400), False),
+    (_case("wu_d64_max3", "bf16", 2, 8, 4, 64, 52000, 32, wl.POOL_MAX, 3, 300), False),
+    (_case("wu_value_norm_rounds", "bf16", 2, 8, 4, 128, 50000, 32, wl.POOL_AVG, 7, 300), True),
+    # fewer rounds, and none at all
+    (_case("wu_gqa3_two_rounds", "bf16", 1, 6, 2, 128, 100000, 32, wl.POOL_AVG, 5, 500), False),
     (_case("wu_short", "bf16", 2, 8, 2, 128, 1000, 32, wl.POOL_AVG, 7, 200), False),           # tails only
-    # shapes the fused pass does not take: they run the two steps through the scratch buffer
-    (_case("wu_avg9", "bf16", 1, 8, 2, 128, 20000, 32, wl.POOL_AVG, 9, 300), False),            # radius 4
     (_case("wu_value_norm", "bf16", 1, 8, 2, 128, 20000, 32, wl.POOL_AVG, 7, 300), True),
     (_case("wu_value_norm_max_gqa3", "bf16", 2, 6, 2, 128, 9000, 32, wl.POOL_MAX, 5, 200), True),
+    # shapes the fused pass does not take: they run the two steps through the scratch buffer
+    (_case("wu_avg9", "bf16", 1, 8, 2, 128, 20000, 32, wl.POOL_AVG, 9, 300), False),            # radius 4
     (_case("wu_w64", "bf16", 1, 4, 2, 128, 20000, 64, wl.POOL_MAX, 7, 300), False),             # two tiles per head
     (_case("wu_odd_prefix", "bf16", 1, 4, 2, 128, 20000, 30, wl.POOL_AVG, 7, 300), False),      # P % 4 != 0
     (_case("wu_f32", "f32", 1, 4, 4, 64, 2048, 32, wl.POOL_AVG, 7, 200, shares=True), False),
