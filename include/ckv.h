@@ -130,6 +130,26 @@ ckv_status ckv_window_lse(const ckv_params *params, const void *q_win, const voi
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ckv_window_lse for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation. Same arguments, same
+ * kernels and bit-identical results as ckv_window_lse; the row partials of the pass live in a device
+ * array inside the library (CKV_STATIC_SCRATCH_BYTES per GPU the library runs on, held until the process
+ * ends) instead of a workspace. Neither this call nor anything it calls allocates or frees memory. The
+ * first call on a device looks the array's address up (once per device).
+ *
+ * Returns CKV_EWORKSPACE, before anything is launched, when the shape needs more than the array holds:
+ * ckv_window_lse_static_bytes(params) gives the need (0 for invalid params); it is
+ * 8 bytes * batch * Hkv * (query rows of a KV head, padded to whole 32-row tiles) * (workgroups along
+ * the key axis), e.g. 256 KiB for batch 16, 8 KV heads, 4 x 32 query rows at T = 32768.
+ * Every call on one GPU uses that GPU's one array, whose contents are undefined between calls: calls
+ * that overlap on one GPU (two streams, two threads) race; calls in stream order on one stream do not.
+ */
+#define CKV_STATIC_SCRATCH_BYTES (4u << 20)
+size_t ckv_window_lse_static_bytes(const ckv_params *params);
+ckv_status ckv_window_lse_static(const ckv_params *params, const void *q_win, const void *k, float *lse,
+                                 void *hip_stream);
+
+/*
  * Pooling, compiled-table lookups and budgets (paper Eq. 6 weighted max over heads, Sec. 4.3 gate
  * lookup, Alg. 1 Stages 2-3 up to the threshold; the 1-D pooling and the per-head budget split are
  * the build's workload definition, not the paper's).

@@ -20,7 +20,7 @@ POOL_NONE, POOL_AVG, POOL_MAX = 0, 1, 2
 FLAG_VALUE_NORM = 1
 FLAG_GROUP_MASS = 8         # ckv_window_scores writes per-KV-head sums [Bz,Hkv,T] (layer-shared mode)
 
-EXPORTS = ("ckv_workspace_bytes", "ckv_window_lse", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
+EXPORTS = ("ckv_workspace_bytes", "ckv_window_lse", "ckv_window_lse_static_bytes", "ckv_window_lse_static", "ckv_window_scores", "ckv_window_utility", "ckv_apply_tables", "ckv_select_topk",
            "ckv_compact_kv", "ckv_alpha_accumulate", "ckv_risk_struct", "ckv_shared_utility", "ckv_compact_kv_shared",
            "ckv_decode_workspace_bytes", "ckv_decode_attention", "ckv_discarded_mass", "ckv_map_table_depth",
            "ckv_status_string")
@@ -62,6 +62,10 @@ def load(path: Optional[Path] = None):
     lib.ckv_window_scores.restype = ctypes.c_int
     lib.ckv_window_lse.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ckv_window_lse.restype = ctypes.c_int
+    lib.ckv_window_lse_static_bytes.argtypes = [pp]
+    lib.ckv_window_lse_static_bytes.restype = ctypes.c_size_t
+    lib.ckv_window_lse_static.argtypes = [pp, vp, vp, vp, vp]
+    lib.ckv_window_lse_static.restype = ctypes.c_int
     lib.ckv_window_utility.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp,
                                        vp, vp, ctypes.c_size_t, vp]
     lib.ckv_window_utility.restype = ctypes.c_int
@@ -163,6 +167,19 @@ def ckv_window_lse(params, q_win, k, lse, workspace, stream=None):
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().ckv_window_lse(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(lse), _ptr(workspace),
                                  nbytes, _stream(stream)), "ckv_window_lse")
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def ckv_window_lse_static_bytes(params: CkvParams) -> int:
+    return int(load().ckv_window_lse_static_bytes(ctypes.byref(params)))
+
+
+def ckv_window_lse_static(params, q_win, k, lse, stream=None):
+    """ckv_window_lse without a workspace argument (the library's own device array holds the scratch)."""
+    _check(load().ckv_window_lse_static(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(lse), _stream(stream)),
+           "ckv_window_lse_static")
 
 
 def ckv_apply_tables(params, scores, vnorm_ratio, w_head, head_share, t_gate, n_ent, n_ppl, risk_bins,

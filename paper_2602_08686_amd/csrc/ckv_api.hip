@@ -3,6 +3,8 @@
 // the caller's stream or returns an error before the first launch.
 #include <math.h>
 
+#include <mutex>
+
 #include "ckv_internal.h"
 
 namespace ckv {
@@ -163,6 +165,62 @@ extern "C" ckv_status ckv_window_lse(const ckv_params *params, const void *q_win
   if (st != CKV_OK) return st;
   if (launch_window_scores(params, s, w, q_win, k, nullptr, lse, nullptr, (char *)workspace,
                            (hipStream_t)hip_stream) != hipSuccess)
+    return CKV_EHIP;
+  return CKV_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// ckv_window_lse for callers that cannot allocate: the row partials of the scan's first pass live in a
+// device array of the library instead of a caller's workspace. Host code never passes the array's name
+// to a kernel (on the host it is only a stand-in for the symbol): the device address is looked up once
+// per device, with that device current, and kept.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[CKV_STATIC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once known
+
+static hipError_t static_scratch(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+extern "C" size_t ckv_window_lse_static_bytes(const ckv_params *params) {
+  if (validate(params) != CKV_OK) return 0;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  return w.part_bytes;
+}
+
+extern "C" ckv_status ckv_window_lse_static(const ckv_params *params, const void *q_win, const void *k, float *lse,
+                                            void *hip_stream) {
+  ckv_status st = validate(params);
+  if (st != CKV_OK) return st;
+  if (!q_win || !k || !lse) return CKV_EINVAL;
+  Shape s;
+  Workspace w;
+  derive(params, &s);
+  layout(params, s, &w);
+  // only the row partials are scratch here (they sit first in the layout); LSE goes to the caller's buffer
+  if (w.part_off != 0 || w.part_bytes > (size_t)CKV_STATIC_SCRATCH_BYTES) return CKV_EWORKSPACE;
+  void *ptr = nullptr;
+  if (static_scratch(&ptr) != hipSuccess) return CKV_EHIP;
+  if (launch_window_scores(params, s, w, q_win, k, nullptr, lse, nullptr, (char *)ptr, (hipStream_t)hip_stream) !=
+      hipSuccess)
     return CKV_EHIP;
   return CKV_OK;
 }

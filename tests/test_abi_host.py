@@ -219,3 +219,14 @@ def test_depth_mapping_is_validated_on_the_host():
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         B.load(tmp_path / "libckv.so")
+
+
+def test_static_scratch_rejects_shapes_beyond_its_array():
+    lib = B.load()
+    # 64 batch elements x 8 KV heads x 128 rows x 8 workgroups along the keys x 8 bytes > 4 MiB
+    p = B.make_params(batch=64, n_q_heads=32, n_kv_heads=8, head_dim=128, seq_len=1 << 20, window=32, dtype="bf16",
+                      pool=B.POOL_AVG, pool_kernel=7, budget=512, cap=4096)
+    need = B.ckv_window_lse_static_bytes(p)
+    assert need > B.STATIC_SCRATCH_BYTES
+    d = ctypes.c_void_p(256)
+    assert lib.ckv_window_lse_static(ctypes.byref(p), d, d, d, None) == B.CKV_EWORKSPACE
