@@ -185,7 +185,7 @@ ckv_status ckv_apply_tables(const ckv_params *params, const float *scores, const
  * ckv_window_scores followed by ckv_apply_tables as ONE call that does not materialise the per-head
  * window mass: same definitions, same utility / budget / tau (within fp32 rounding of the pooled sum),
  * for callers that only need what the selection consumes (paper Alg. 1 from the window scan up to the
- * threshold). Where the shape allows it (bf16, W <= 32, G*ceil(W/32) <= 4, pooling kernel <= 7, T and
+ * threshold). Where the shape allows it (bf16, W <= 64, G*ceil(W/32) <= 8, pooling kernel <= 7, T and
  * P multiples of four) the scan's second pass pools, weights and maximises over the group's heads on
  * chip and writes [Bz,Hkv,P] instead of [Bz,Hq,T] (with CKV_FLAG_VALUE_NORM the ratio, common to a
  * group's heads, then multiplies the group maximum); otherwise the two steps run one after the other

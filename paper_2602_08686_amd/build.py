@@ -10,7 +10,9 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB = PKG / "libckv.so"
-SCAN_SOURCES = ["ckv_scan_bf16_d128.hip", "ckv_scan_bf16_d64.hip", "ckv_scan_f32_d64.hip", "ckv_scan_f32_d128.hip"]
+SCAN_SOURCES = ["ckv_scan_bf16_d128_nq78.hip", "ckv_scan_bf16_d128_nq56.hip", "ckv_scan_bf16_d64_nq78.hip",
+                "ckv_scan_bf16_d64_nq56.hip", "ckv_scan_bf16_d128.hip", "ckv_scan_bf16_d64.hip", "ckv_scan_f32_d64.hip",
+                "ckv_scan_f32_d128.hip"]
 SOURCES = SCAN_SOURCES + ["ckv_api.hip", "ckv_scores.hip", "ckv_tables.hip", "ckv_select.hip", "ckv_gather.hip", "ckv_shared.hip", "ckv_decode.hip"]
 # Packed-FP32 instructions are switched off for the device pass (some forms have given wrong
 # results on the target machines); the host pass does not know the feature and says so, harmlessly.

@@ -38,7 +38,7 @@ ckv_status validate(const ckv_params *p) {
   for (int i = 0; i < 3; ++i)
     if (p->q_stride[i] % per16 || p->k_stride[i] % per16 || p->v_stride[i] % per16) return CKV_EINVAL;
   if (p->head_dim != 64 && p->head_dim != 128) return CKV_EUNSUPPORTED;
-  if (p->window > kMaxQTiles * kTile) return CKV_EUNSUPPORTED;
+  if (p->window > kMaxWindowTiles * kTile) return CKV_EUNSUPPORTED;
   if ((int64_t)p->batch * p->n_kv_heads > 65535) return CKV_EUNSUPPORTED;  // grid.y
   if (p->seq_len > (1 << 24)) return CKV_EUNSUPPORTED;
   // the staged scan addresses the 32 rows of a key tile with 32-bit offsets
@@ -59,9 +59,10 @@ void derive(const ckv_params *p, Shape *s) {
   s->esize = p->dtype == CKV_BF16 ? 2 : 4;
   s->WT = (s->W + kTile - 1) / kTile;
   s->n_tiles = s->G * s->WT;
-  // Tiles a wave keeps in registers: four when a row is 256 bytes or less, whole heads only; rows
-  // of 512 bytes (f32, d = 128) leave room for one head's tiles only.
-  const int budget_tiles = s->d * s->esize <= 256 ? kMaxQTiles : 1;
+  // Tiles a wave keeps in registers, whole heads only: eight for bf16 (a wave alone on its SIMD has 512
+  // registers, and the matrix cores read operands from either half), four for f32 rows of 256 bytes,
+  // one head's tiles for f32 rows of 512 bytes.
+  const int budget_tiles = p->dtype == CKV_BF16 ? kMaxQTiles : s->d * s->esize <= 256 ? kMaxQTilesF32 : 1;
   const int per_wave_max = budget_tiles >= s->WT ? (budget_tiles / s->WT) * s->WT : s->WT;
   s->n_groups = (s->n_tiles + per_wave_max - 1) / per_wave_max;
   int nq = (s->n_tiles + s->n_groups - 1) / s->n_groups;
@@ -141,7 +142,7 @@ extern "C" ckv_status ckv_window_scores(const ckv_params *params, const void *q_
   st = workspace_ok(w, workspace, workspace_bytes);
   if (st != CKV_OK) return st;
   // the group-mass output exists where one wave holds all query heads of a KV head, one tile each
-  if ((params->flags & CKV_FLAG_GROUP_MASS) && !(params->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1))
+  if ((params->flags & CKV_FLAG_GROUP_MASS) && !(params->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1 && s.NQ <= 4))
     return CKV_EUNSUPPORTED;
   hipStream_t stream = (hipStream_t)hip_stream;
   if (launch_window_scores(params, s, w, q_win, k, lse, nullptr, scores, (char *)workspace, stream) != hipSuccess)
@@ -245,13 +246,13 @@ extern "C" ckv_status ckv_apply_tables(const ckv_params *params, const float *sc
 }
 
 // Whether ckv_window_utility can run its fused second pass for this call (else it runs the two
-// unfused steps through the scratch buffer): the pipelined bf16 kernels with one 32-row tile per head
-// and all query tiles of a group in one wave, pooling kernels of at most 7 taps, rows that keep the
+// unfused steps through the scratch buffer): the pipelined bf16 kernels with at most two 32-row tiles per
+// head and all query tiles of a group in one wave (at most eight), pooling kernels of at most 7 taps, rows that keep the
 // 128-bit and 64-bit accesses aligned. With the value-norm flag the ratio, which is common to a group's
 // heads and non-negative, multiplies the group maximum afterwards (in the value-norm scaling pass).
 static bool utility_fast_path(const ckv_params *p, const Shape &s, const float *scratch, const float *utility) {
   const int kernel = p->pool == CKV_POOL_NONE ? 1 : p->pool_kernel;
-  return p->dtype == CKV_BF16 && s.n_groups == 1 && s.WT == 1 && kernel / 2 <= 3 && s.T % 4 == 0 && s.P % 4 == 0 && s.P > 0 && (uintptr_t)scratch % 16 == 0 &&
+  return p->dtype == CKV_BF16 && s.n_groups == 1 && s.WT <= 2 && kernel / 2 <= 3 && s.T % 4 == 0 && s.P % 4 == 0 && s.P > 0 && (uintptr_t)scratch % 16 == 0 &&
          (uintptr_t)utility % 16 == 0 && (int64_t)s.Hkv * s.P < (1 << 29);
 }
 

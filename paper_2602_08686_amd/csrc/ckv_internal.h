@@ -12,7 +12,9 @@ namespace ckv {
 
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kTile = 32;          // MFMA 32x32 tile edge: query rows and keys per tile
-constexpr int kMaxQTiles = 4;      // query-row tiles a wave keeps in registers
+constexpr int kMaxQTiles = 8;      // query-row tiles a wave keeps in registers (bf16; f32 kernels: kMaxQTilesF32)
+constexpr int kMaxQTilesF32 = 4;
+constexpr int kMaxWindowTiles = 4; // 32-row tiles per query head: W <= 128
 constexpr int kScoreWaves = 4;     // waves per workgroup in the scan kernels
 constexpr int kComputeUnits = 256; // MI355X
 constexpr int kSelectThreads = 1024;

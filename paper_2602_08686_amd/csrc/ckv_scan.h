@@ -328,7 +328,7 @@ __global__ void __launch_bounds__(kScoreWaves *kWave, 2) colsum_kernel(ScoreArgs
       if (i % a.WT) continue;
       float v = cs[i];
 #pragma unroll
-      for (int e = 1; e < kMaxQTiles; ++e)
+      for (int e = 1; e < kMaxWindowTiles; ++e)
         if (e < a.WT && i + e < NQ) v += cs[(i + e) < NQ ? (i + e) : i];
       const int tile = bc.grp * NQ + i;
       if (tile < a.n_tiles && hh == 0 && kt < a.T) {
@@ -480,6 +480,13 @@ __device__ __forceinline__ void interleave_hint() {
   }
 }
 
+// Key tiles per unrolled body of the pipelines. Up to four query tiles per wave the body is a whole ring
+// cycle (every ring image address is an immediate). Beyond that a body of four tiles holds so many
+// scheduling-hint groups that the compiler's solver for them needs minutes per kernel; half a cycle
+// keeps it at seconds, and the ring image of a body's first tile becomes a run-time (scalar) value.
+__host__ __device__ constexpr int unroll_tiles(int nq) { return nq > 4 ? 2 : kRing; }
+static_assert(kRing % 2 == 0, "half a ring cycle starts at an even image");
+
 // Geometry of a wave's key range: wave-uniform values live in scalar registers.
 struct WaveRange {
   int wave, t_begin, t_end, n_full;
@@ -507,9 +514,11 @@ struct Staged {
   int64_t tile_stride;
   uint32_t lds_ring;       // LDS address of this wave's first image
 
-  // Starts the loads of Q (wave w moves query tile w into the last image of its ring) and of the first
-  // three key tiles, then hands every wave all NQ query tiles in registers. jrow[i] = window row of
-  // tile i, row m, or -1 on padding.
+  // Starts the loads of Q (wave w moves query tiles w and w + 4 into the last images of its ring) and of the
+  // first key tiles, then hands every wave all NQ query tiles in registers; on return the wave's first
+  // three key tiles are in flight, in order. jrow[i] = window row of tile i, row m, or -1 on padding.
+  static constexpr int QI = (NQ + kScoreWaves - 1) / kScoreWaves;  // ring images per wave that first hold Q
+  static_assert(QI >= 1 && QI <= kRing - 2, "query tiles pass through the ring's last images");
   __device__ __forceinline__ void start(const ScoreArgs &a, const BlockCoord &bc, const WaveRange &wr, Ring &ring,
                                         int lane, int m, int hh, chunk_t (&qf)[NQ][NCH], int (&jrow)[NQ]) {
 #pragma unroll
@@ -526,24 +535,28 @@ struct Staged {
     klast = kcur + max(wr.n_full - 1, 0) * tile_stride;
     lds_ring = (uint32_t)(uintptr_t)&ring[wr.wave][0][0];
 
-    if (wr.wave < NQ) {
-      const int tile = min(bc.grp * NQ + wr.wave, a.n_tiles - 1);
-      const char *qhead = a.q + bc.b * a.qs_b + (bc.g * a.G + tile / a.WT) * a.qs_h;
-      const int j0 = (tile % a.WT) * kTile;
 #pragma unroll
-      for (int i = 0; i < G::NDMA; ++i) {
-        int r, kappa;
-        dma_source<G>(i, lane, r, kappa);
-        const char *src = qhead + (int64_t)min(j0 + r, a.W - 1) * a.qs_w + kappa * 16;
-        __builtin_amdgcn_global_load_lds((glb_void_t *)src,
-                                         (lds_void_t *)(uintptr_t)(ring[wr.wave][kRing - 1] + i * 1024), 16, 0, 0);
+    for (int qi = 0; qi < QI; ++qi) {
+      if (wr.wave + qi * kScoreWaves < NQ) {
+        const int tile = min(bc.grp * NQ + wr.wave + qi * kScoreWaves, a.n_tiles - 1);
+        const char *qhead = a.q + bc.b * a.qs_b + (bc.g * a.G + tile / a.WT) * a.qs_h;
+        const int j0 = (tile % a.WT) * kTile;
+#pragma unroll
+        for (int i = 0; i < G::NDMA; ++i) {
+          int r, kappa;
+          dma_source<G>(i, lane, r, kappa);
+          const char *src = qhead + (int64_t)min(j0 + r, a.W - 1) * a.qs_w + kappa * 16;
+          __builtin_amdgcn_global_load_lds((glb_void_t *)src,
+                                           (lds_void_t *)(uintptr_t)(ring[wr.wave][kRing - 1 - qi] + i * 1024), 16, 0, 0);
+        }
       }
     }
+    constexpr int N_PRE = kRing - QI;  // key tiles whose images are free while Q passes through
     if (wr.n_full > 0) {
 #pragma unroll
-      for (int d = 0; d < kRing - 1; ++d)
+      for (int d = 0; d < N_PRE; ++d)
         dma_tile<G>(d < wr.n_full ? kcur + d * tile_stride : klast, voff, lds_ring + d * G::TILE);
-      wait_vm<(kRing - 1) * G::NDMA>();  // Q has landed, the key tiles may still be on their way
+      wait_vm<N_PRE * G::NDMA>();  // Q has landed, the key tiles may still be on their way
     } else {
       wait_vm<0>();
     }
@@ -554,13 +567,18 @@ struct Staged {
       const int j = (tile % a.WT) * kTile + m;
       const bool valid = tile < a.n_tiles && j < a.W;
       jrow[i] = valid ? j : -1;
-      read_image<G>(qf[i], ring[i][kRing - 1], roff);
+      read_image<G>(qf[i], ring[i % kScoreWaves][kRing - 1 - i / kScoreWaves], roff);
       if (!valid) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) qf[i][c] = chunk_t{0u, 0u, 0u, 0u};
       }
     }
     __syncthreads();  // the images that held Q are free for key tiles from here on
+    if (wr.n_full > 0) {
+#pragma unroll
+      for (int d = N_PRE; d < kRing - 1; ++d)
+        dma_tile<G>(d < wr.n_full ? kcur + d * tile_stride : klast, voff, lds_ring + d * G::TILE);
+    }
   }
 
   // Load of the tile three ahead of the one at kcur (tile index t + 3) into ring image `slot`; past
@@ -601,20 +619,23 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) rowstats_lds_kernel(ScoreA
     read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
     mma_chain<DT, NCH>(acc[0], kreg[0], qf[0]);
   }
-  for (int t0 = 0; t0 < n_piped; t0 += kRing) {
+  constexpr int UR = unroll_tiles(NQ);
+  for (int t0 = 0; t0 < n_piped; t0 += UR) {
+    const int slot0 = UR == kRing ? 0 : (t0 & (kRing - 1));  // ring image of tile t0
 #pragma unroll
-    for (int u = 0; u < kRing; ++u) {  // tile t0 + u lives in image u and in kreg[u & 1]
-      st.prefetch(t0 + u, wr.n_full, (u + kRing - 1) % kRing);
+    for (int v = 0; v < UR; ++v) {  // tile t0 + v lives in image u and in kreg[v & 1]
+      const int u = slot0 + v;
+      st.prefetch(t0 + v, wr.n_full, (u + kRing - 1) % kRing);
 #pragma unroll
       for (int i = 0; i < NQ; ++i) {
-        const int cur = (u * NQ + i) & 1;  // accumulator set holding this pair's logits
+        const int cur = (v * NQ + i) & 1;  // accumulator set holding this pair's logits
         if (i == READ_AT) {
-          wait_vm<(kRing - 2) * G::NDMA>();  // tile t0 + u + 1 has landed
-          read_image<G>(kreg[(u + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
+          wait_vm<(kRing - 2) * G::NDMA>();  // tile t0 + v + 1 has landed
+          read_image<G>(kreg[(v + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
         }
         // logits of the next pair; the last pair of a key tile already starts the next key tile
-        if (i + 1 < NQ) mma_chain<DT, NCH>(acc[cur ^ 1], kreg[u & 1], qf[i + 1]);
-        else mma_chain<DT, NCH>(acc[cur ^ 1], kreg[(u + 1) & 1], qf[0]);
+        if (i + 1 < NQ) mma_chain<DT, NCH>(acc[cur ^ 1], kreg[v & 1], qf[i + 1]);
+        else mma_chain<DT, NCH>(acc[cur ^ 1], kreg[(v + 1) & 1], qf[0]);
         rowstats_update<false>(acc[cur], a.c2, 0, hh, 0, rm[i], rl[i]);
         if (i == READ_AT) interleave_hint<N_MFMA, 8, NCH>();
         else interleave_hint<N_MFMA, 8, 0>();
@@ -887,11 +908,12 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
   __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, out), rsrc_u, off_u, 0, kOutStoreAux);
   // carry: the block's last kUtilCarry values move in front of the rows for the next block
   constexpr int PER = kUtilCarry / 4;  // 128-bit pieces per head
-  static_assert(PER * NH <= kWave, "one piece per lane");
-  if (lane < PER * NH) {
-    float *row = rows + (lane / PER) * kUtilRow;
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(row + BLK + 4 * (lane % PER));
-    *reinterpret_cast<f32x4 *>(row + 4 * (lane % PER)) = v;
+  static_assert(PER * NH <= 2 * kWave, "at most two pieces per lane");
+#pragma unroll
+  for (int piece = lane; piece < PER * NH; piece += kWave) {
+    float *row = rows + (piece / PER) * kUtilRow;
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(row + BLK + 4 * (piece % PER));
+    *reinterpret_cast<f32x4 *>(row + 4 * (piece % PER)) = v;
   }
 }
 
@@ -966,24 +988,30 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
     mma_chain<DT, NCH>(acc[0], qf[0], kreg[0]);
     bias[0].add(acc[0], ones);
   }
-  for (int t0 = 0; t0 < n_piped; t0 += kRing) {
+  constexpr int UR = unroll_tiles(NQ);
+  for (int t0 = 0; t0 < n_piped; t0 += UR) {
+    const int slot0 = UR == kRing ? 0 : (t0 & (kRing - 1));  // ring image of tile t0
 #pragma unroll
-    for (int u = 0; u < kRing; ++u) {
-      st.prefetch(t0 + u, wr.n_full, (u + kRing - 1) % kRing);
+    for (int v = 0; v < UR; ++v) {
+      const int u = slot0 + v;
+      st.prefetch(t0 + v, wr.n_full, (u + kRing - 1) % kRing);
       float cs[NQ];
 #pragma unroll
       for (int i = 0; i < NQ; ++i) {
-        const int cur = (u * NQ + i) & 1;
+        const int cur = (v * NQ + i) & 1;
         if (i == READ_AT) {
-          if (u < 2) wait_vm<(kRing - 2) * G::NDMA + N_STORES>();  // tile t0 + u + 1 has landed
+          // tile t0 + v + 1 has landed. In the first half of a ring cycle the previous cycle's stores were
+          // issued after its load and may still be in flight; where the half is only known at run time the
+          // wait does not allow for them (stricter, never wrong).
+          if (UR == kRing && v < 2) wait_vm<(kRing - 2) * G::NDMA + N_STORES>();
           else wait_vm<(kRing - 2) * G::NDMA>();
-          read_image<G>(kreg[(u + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
+          read_image<G>(kreg[(v + 1) & 1], ring[wr.wave][(u + 1) % kRing], st.roff);
         }
         if (i + 1 < NQ) {
-          mma_chain<DT, NCH>(acc[cur ^ 1], qf[i + 1], kreg[u & 1]);  // rows: query rows, cols: keys
+          mma_chain<DT, NCH>(acc[cur ^ 1], qf[i + 1], kreg[v & 1]);  // rows: query rows, cols: keys
           bias[i + 1].add(acc[cur ^ 1], ones);
         } else {
-          mma_chain<DT, NCH>(acc[cur ^ 1], qf[0], kreg[(u + 1) & 1]);
+          mma_chain<DT, NCH>(acc[cur ^ 1], qf[0], kreg[(v + 1) & 1]);
           bias[0].add(acc[cur ^ 1], ones);
         }
         cs[i] = colsum_weights<false>(acc[cur], a.c2, hh, 0);
@@ -994,10 +1022,13 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
       else stage_column_sums<NQ, WT>(cs, a.norm, stage, u, m, hh);
       st.kcur += st.tile_stride;
     }
-    if constexpr (UTIL)
-      flush_utility<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, t0 == 0, t0 + kRing >= n_piped, lane, rsrc, rsrc_u, wgt);
-    else if constexpr (GSUM) flush_group_sums<NQ>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
-    else flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + t0 * kTile, lane, rsrc);
+    if (UR == kRing || slot0 + UR == kRing) {  // a ring cycle is complete
+      const int c0 = t0 + UR - kRing;          // its first tile
+      if constexpr (UTIL)
+        flush_utility<NQ, WT>(a, bc, stage, wr.t_begin + c0 * kTile, c0 == 0, c0 + kRing >= n_piped, lane, rsrc, rsrc_u, wgt);
+      else if constexpr (GSUM) flush_group_sums<NQ>(a, bc, stage, wr.t_begin + c0 * kTile, lane, rsrc);
+      else flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + c0 * kTile, lane, rsrc);
+    }
   }
   wait_vm<0>();
   for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
@@ -1036,7 +1067,7 @@ static void launch_rowstats(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 
 template <int DT, int NQ>
 static bool colsum_is_staged(const Shape &s) {
   if (DT != CKV_BF16) return false;
-  return s.WT == 1 || (NQ % 2 == 0 && s.WT == 2) || (NQ == 3 && s.WT == 3) || (NQ == 4 && s.WT == 4);
+  return s.WT >= 1 && s.WT <= kMaxWindowTiles && NQ % s.WT == 0;
 }
 
 template <int DT, int DH, int NQ>
@@ -1045,23 +1076,25 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
     // NQ is a multiple of WT (whole heads per wave)
     if (s.WT == 1) {
       if (a.utility) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1, true>), grid, block, 0, stream, a);
-      else if (a.group_sum) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1, false, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1>), grid, block, 0, stream, a);
+      else if (a.group_sum) {
+        if constexpr (NQ <= 4) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1, false, true>), grid, block, 0, stream, a);
+      } else hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 1>), grid, block, 0, stream, a);
       return;
     }
     if constexpr (NQ % 2 == 0) {
       if (s.WT == 2) {
-        hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 2>), grid, block, 0, stream, a);
+        if (a.utility) hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 2, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 2>), grid, block, 0, stream, a);
         return;
       }
     }
-    if constexpr (NQ == 3) {
+    if constexpr (NQ % 3 == 0) {
       if (s.WT == 3) {
         hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 3>), grid, block, 0, stream, a);
         return;
       }
     }
-    if constexpr (NQ == 4) {
+    if constexpr (NQ % 4 == 0) {
       if (s.WT == 4) {
         hipLaunchKernelGGL((colsum_lds_kernel<DT, DH, NQ, 4>), grid, block, 0, stream, a);
         return;
@@ -1071,21 +1104,30 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
   hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
 }
 
-template <int DT, int DH>
+// Launches for the query-tile counts NQ_LO..NQ_HI (the instantiations are spread over several translation
+// units, each covering a range, to keep compile times apart).
+template <int DT, int DH, int NQ_LO, int NQ_HI>
 static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream) {
   const int units = s.Bz * s.Hkv;
   const dim3 grid((unsigned)((size_t)units * s.n_groups * s.n_chunks)), block(kScoreWaves * kWave);
-#define CKV_LAUNCH_NQ(NQ)                                                        \
-  case NQ:                                                                       \
-    a.lse_from_part = need_lse && need_scores && colsum_is_staged<DT, NQ>(s);    \
-    if (need_lse) launch_rowstats<DT, DH, NQ>(s, a, grid, block, stream);        \
-    if (need_scores) launch_colsum<DT, DH, NQ>(s, a, grid, block, stream);       \
-    break;
+#define CKV_LAUNCH_NQ(NQ)                                                          \
+  case NQ:                                                                         \
+    if constexpr (NQ >= NQ_LO && NQ <= NQ_HI) {                                    \
+      a.lse_from_part = need_lse && need_scores && colsum_is_staged<DT, NQ>(s);    \
+      if (need_lse) launch_rowstats<DT, DH, NQ>(s, a, grid, block, stream);        \
+      if (need_scores) launch_colsum<DT, DH, NQ>(s, a, grid, block, stream);       \
+      break;                                                                       \
+    }                                                                              \
+    return hipErrorInvalidValue;
   switch (s.NQ) {
     CKV_LAUNCH_NQ(1)
     CKV_LAUNCH_NQ(2)
     CKV_LAUNCH_NQ(3)
     CKV_LAUNCH_NQ(4)
+    CKV_LAUNCH_NQ(5)
+    CKV_LAUNCH_NQ(6)
+    CKV_LAUNCH_NQ(7)
+    CKV_LAUNCH_NQ(8)
     default: return hipErrorInvalidValue;
   }
 #undef CKV_LAUNCH_NQ
@@ -1093,15 +1135,18 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, b
 }
 
 
-// One definition per (element type, head size), each in a translation unit of its own.
-hipError_t launch_scores_bf16_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   hipStream_t stream);
-hipError_t launch_scores_bf16_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   hipStream_t stream);
-hipError_t launch_scores_f32_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   hipStream_t stream);
-hipError_t launch_scores_f32_d64(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                   hipStream_t stream);
+// One definition per (element type, head size, range of query-tile counts), each in a translation unit of
+// its own.
+#define CKV_DECLARE_SCAN(name) \
+  hipError_t name(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores, hipStream_t stream)
+CKV_DECLARE_SCAN(launch_scores_bf16_d128);       // 1..4 query tiles per wave
+CKV_DECLARE_SCAN(launch_scores_bf16_d128_nq56);
+CKV_DECLARE_SCAN(launch_scores_bf16_d128_nq78);
+CKV_DECLARE_SCAN(launch_scores_bf16_d64);
+CKV_DECLARE_SCAN(launch_scores_bf16_d64_nq56);
+CKV_DECLARE_SCAN(launch_scores_bf16_d64_nq78);
+CKV_DECLARE_SCAN(launch_scores_f32_d128);
+CKV_DECLARE_SCAN(launch_scores_f32_d64);
 
 }  // namespace ckv
 #endif

@@ -1,9 +1,8 @@
-// Scan kernels for bf16, d128: see ckv_scan.h.
+// Scan kernels for bf16, d = 128, 1-4 query tiles per wave: see ckv_scan.h.
 #include "ckv_scan.h"
 
 namespace ckv {
-hipError_t launch_scores_bf16_d128(const Shape &s, ScoreArgs &a, bool need_lse, bool need_scores,
-                                  hipStream_t stream) {
-  return launch_scores_t<CKV_BF16, 128>(s, a, need_lse, need_scores, stream);
+CKV_DECLARE_SCAN(launch_scores_bf16_d128) {
+  return launch_scores_t<CKV_BF16, 128, 1, 4>(s, a, need_lse, need_scores, stream);
 }
 }  // namespace ckv

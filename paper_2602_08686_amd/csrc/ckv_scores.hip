@@ -35,8 +35,14 @@ hipError_t launch_window_scores(const ckv_params *p, const Shape &s, const Works
   a.inv_kernel = fuse ? fuse->inv_kernel : 1.0f;
   const bool need_lse = lse_in == nullptr, need_scores = scores != nullptr;
   if (p->dtype == CKV_BF16) {
-    if (s.d == 128) return launch_scores_bf16_d128(s, a, need_lse, need_scores, stream);
-    return launch_scores_bf16_d64(s, a, need_lse, need_scores, stream);
+    if (s.d == 128) {
+      if (s.NQ <= 4) return launch_scores_bf16_d128(s, a, need_lse, need_scores, stream);
+      if (s.NQ <= 6) return launch_scores_bf16_d128_nq56(s, a, need_lse, need_scores, stream);
+      return launch_scores_bf16_d128_nq78(s, a, need_lse, need_scores, stream);
+    }
+    if (s.NQ <= 4) return launch_scores_bf16_d64(s, a, need_lse, need_scores, stream);
+    if (s.NQ <= 6) return launch_scores_bf16_d64_nq56(s, a, need_lse, need_scores, stream);
+    return launch_scores_bf16_d64_nq78(s, a, need_lse, need_scores, stream);
   }
   if (s.d == 128) return launch_scores_f32_d128(s, a, need_lse, need_scores, stream);
   return launch_scores_f32_d64(s, a, need_lse, need_scores, stream);

@@ -30,8 +30,14 @@ SCORE_CASES = [
     _small("bf16_mha", "bf16", 1, 8, 8, 128, 2048, 32, sink_scale=8.0),
     _small("bf16_gqa4", "bf16", 2, 8, 2, 128, 4133, 32, pareto_frac=0.05),   # NQ=4, ragged tail
     _small("bf16_gqa4_w64", "bf16", 1, 8, 2, 128, 3000, 64, needles=4),      # two tiles per head
-    _small("bf16_gqa7", "bf16", 1, 7, 1, 128, 2500, 32, head_key_scale=True),  # two groups (4+3)
-    _small("bf16_gqa5_w48", "bf16", 1, 5, 1, 128, 1500, 48),                 # WT=2, padded rows
+    _small("bf16_gqa7", "bf16", 1, 7, 1, 128, 2500, 32, head_key_scale=True),  # seven tiles in one wave
+    _small("bf16_gqa5_w48", "bf16", 1, 5, 1, 128, 1500, 48),                 # WT=2, padded rows, groups of 6 + 4 tiles
+    _small("bf16_gqa5", "bf16", 2, 10, 2, 128, 1700, 32),                    # five tiles per wave
+    _small("bf16_gqa6_d64", "bf16", 1, 6, 1, 64, 2100, 32),                  # six tiles, 128-byte rows
+    _small("bf16_gqa8", "bf16", 1, 16, 2, 128, 1900, 32, sink_scale=8.0),    # eight tiles, one per head
+    _small("bf16_gqa12", "bf16", 1, 12, 1, 128, 1300, 32),                   # two groups of six tiles
+    _small("bf16_gqa2_w96", "bf16", 1, 4, 2, 128, 1400, 96, B_=200),         # three tiles per head, six per wave
+    _small("bf16_gqa2_w128_d64", "bf16", 1, 2, 1, 64, 1200, 128, B_=200),    # four tiles per head, eight per wave
     _small("bf16_d64", "bf16", 1, 4, 2, 64, 1111, 32),
     _small("bf16_w1", "bf16", 1, 2, 2, 128, 500, 1),
     _small("bf16_all_window", "bf16", 1, 2, 1, 128, 32, 32, B_=32),         # P = 0
@@ -66,11 +72,18 @@ def test_window_scores_match_oracle(w):
 # the scan kernels' four-tile software pipeline (the cases above mostly take its masked tail path):
 # odd group sizes, several tiles per head, 128-byte rows, ragged ends.
 PIPELINE_CASES = [
-    _small("long_gqa7", "bf16", 1, 7, 1, 128, 70001, 32, pareto_frac=0.05),       # groups of 4 + 3 heads
+    _small("long_gqa7", "bf16", 1, 7, 1, 128, 70001, 32, pareto_frac=0.05),       # seven tiles per wave
+    _small("long_gqa5", "bf16", 1, 5, 1, 128, 90001, 32),                         # five tiles per wave
+    _small("long_gqa6_d64", "bf16", 1, 6, 1, 64, 80002, 32),                      # six tiles, 128-byte rows
+    _small("long_gqa8", "bf16", 1, 8, 1, 128, 70003, 32, sink_scale=8.0),         # eight tiles, one per head
+    _small("long_gqa3_w64", "bf16", 1, 3, 1, 128, 60000, 64),                     # six tiles, two per head
+    _small("long_gqa2_w96", "bf16", 1, 2, 1, 128, 60001, 96, B_=300),             # six tiles, three per head
+    _small("long_gqa2_w128", "bf16", 1, 4, 2, 128, 50000, 128, B_=300),           # eight tiles, four per head
+    _small("long_gqa9", "bf16", 1, 9, 1, 128, 40000, 32),                         # two groups: 5 + 4 tiles
     _small("long_gqa3", "bf16", 1, 3, 1, 128, 140003, 32, sink_scale=8.0),        # three tiles per wave
     _small("long_w64", "bf16", 1, 8, 2, 128, 40000, 64, needles=4),               # two tiles per head
     _small("long_w128", "bf16", 1, 2, 2, 128, 70000, 128, B_=300),                # four tiles per head
-    _small("long_w48_gqa5", "bf16", 1, 5, 1, 128, 50000, 48),                     # padded second tile, 2+2+1 heads
+    _small("long_w48_gqa5", "bf16", 1, 5, 1, 128, 50000, 48),                     # padded second tile, groups of 3 + 2 heads
     _small("long_d64", "bf16", 1, 4, 2, 64, 70003, 32, head_key_scale=True),      # 128-byte rows
     _small("long_mha", "bf16", 1, 2, 2, 128, 66000, 32),                          # one tile per wave
 ]

@@ -39,6 +39,15 @@ CASES = [
     (_case("wu_d64_avg7", "bf16", 2, 16, 4, 64, 70000, 32, wl.POOL_AVG, 7, 400), False),
     (_case("wu_d64_max3", "bf16", 2, 8, 4, 64, 52000, 32, wl.POOL_MAX, 3, 300), False),
     (_case("wu_value_norm_rounds", "bf16", 2, 8, 4, 128, 50000, 32, wl.POOL_AVG, 7, 300), True),
+    # five to eight query tiles per wave, and two tiles per head (W = 64)
+    (_case("wu_gqa7_avg5", "bf16", 2, 14, 2, 128, 66000, 32, wl.POOL_AVG, 5, 600, head_key_scale=True, gate=True), False),
+    (_case("wu_gqa8_max7", "bf16", 1, 16, 2, 128, 140000, 32, wl.POOL_MAX, 7, 500, needles=4), False),
+    (_case("wu_gqa5_avg3_d64", "bf16", 2, 10, 2, 64, 100000, 32, wl.POOL_AVG, 3, 400), False),
+    (_case("wu_gqa6_nopool", "bf16", 4, 6, 1, 128, 100000, 24, wl.POOL_NONE, 1, 300), False),
+    (_case("wu_gqa4_w64_max7", "bf16", 1, 8, 2, 128, 200000, 64, wl.POOL_MAX, 7, 700, needles=6, sink_scale=8.0, shares=True), False),
+    (_case("wu_gqa3_w48_avg7", "bf16", 2, 6, 2, 128, 100000, 48, wl.POOL_AVG, 7, 500), False),
+    (_case("wu_gqa2_w64_avg5_d64", "bf16", 2, 4, 2, 64, 100000, 64, wl.POOL_AVG, 5, 400, shares=True), False),
+    (_case("wu_gqa4_w64_value_norm", "bf16", 4, 8, 2, 128, 50000, 64, wl.POOL_AVG, 7, 300), True),
     # fewer rounds, and none at all
     (_case("wu_gqa3_two_rounds", "bf16", 1, 6, 2, 128, 100000, 32, wl.POOL_AVG, 5, 500), False),
     (_case("wu_short", "bf16", 2, 8, 2, 128, 1000, 32, wl.POOL_AVG, 7, 200), False),           # tails only
@@ -46,7 +55,7 @@ CASES = [
     (_case("wu_value_norm_max_gqa3", "bf16", 2, 6, 2, 128, 9000, 32, wl.POOL_MAX, 5, 200), True),
     # shapes the fused pass does not take: they run the two steps through the scratch buffer
     (_case("wu_avg9", "bf16", 1, 8, 2, 128, 20000, 32, wl.POOL_AVG, 9, 300), False),            # radius 4
-    (_case("wu_w64", "bf16", 1, 4, 2, 128, 20000, 64, wl.POOL_MAX, 7, 300), False),             # two tiles per head
+    (_case("wu_w96", "bf16", 1, 4, 2, 128, 20000, 96, wl.POOL_MAX, 7, 300), False),             # three tiles per head
     (_case("wu_odd_prefix", "bf16", 1, 4, 2, 128, 20000, 30, wl.POOL_AVG, 7, 300), False),      # P % 4 != 0
     (_case("wu_f32", "f32", 1, 4, 4, 64, 2048, 32, wl.POOL_AVG, 7, 200, shares=True), False),
 ]
