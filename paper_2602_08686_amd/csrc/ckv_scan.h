@@ -104,6 +104,13 @@ __device__ __forceinline__ BlockCoord decode_block(const ScoreArgs &a) {
   c.unit = bid / a.n_groups;
   c.b = c.unit / a.Hkv;
   c.g = c.unit % a.Hkv;
+  // wave-uniform by construction; the divisions run on the vector ALU, so say it (addresses derived from
+  // these feed scalar operands)
+  c.chunk = __builtin_amdgcn_readfirstlane(c.chunk);
+  c.grp = __builtin_amdgcn_readfirstlane(c.grp);
+  c.unit = __builtin_amdgcn_readfirstlane(c.unit);
+  c.b = __builtin_amdgcn_readfirstlane(c.b);
+  c.g = __builtin_amdgcn_readfirstlane(c.g);
   return c;
 }
 
@@ -419,6 +426,14 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("" ::: "memory");
 }
 
+// A wave-uniform pointer as a scalar register pair. The compiler may form uniform 64-bit address
+// arithmetic on the vector ALU; operands of the scalar-base loads below must be told apart from that.
+__device__ __forceinline__ const char *uniform_ptr(const char *p) {
+  const uint64_t v = (uint64_t)(uintptr_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Four loads with one M0 write: instruction j reads 16 bytes per lane at sbase + voff_j + 1024 * j
 // and writes them at LDS address lds + 1024 * j + 16 * lane. K is read once per pass and never again
 // before everything else has gone through the caches: the loads are marked non-temporal (streaming),
@@ -529,10 +544,10 @@ struct Staged {
     }
 #pragma unroll
     for (int c = 0; c < NCH; ++c) roff[c] = image_offset<G>(m, c + NCH * hh);
-    kbase = a.k + bc.b * a.ks_b + bc.g * a.ks_h;
-    kcur = kbase + (int64_t)wr.t_begin * a.ks_t;
+    kbase = uniform_ptr(a.k + bc.b * a.ks_b + bc.g * a.ks_h);
+    kcur = uniform_ptr(kbase + (int64_t)wr.t_begin * a.ks_t);
     tile_stride = (int64_t)kTile * a.ks_t;
-    klast = kcur + max(wr.n_full - 1, 0) * tile_stride;
+    klast = uniform_ptr(kcur + max(wr.n_full - 1, 0) * tile_stride);
     lds_ring = (uint32_t)(uintptr_t)&ring[wr.wave][0][0];
 
 #pragma unroll
