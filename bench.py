@@ -2,10 +2,12 @@
 """Benchmark of the prefill-end retention step (window scan + tables + select + gather) on one MI355X.
 
 A step is one pass of the whole hot path over every layer of one synthetic prompt batch: for each
-layer the four C-ABI calls are queued back-to-back on one stream, every layer with its own K/V
-buffers already resident in HBM. The headline value is algorithmic bytes moved per second
+layer the C-ABI calls are queued back-to-back on one stream, every layer with its own K/V, output and
+scratch buffers already resident in HBM. The headline value is algorithmic bytes moved per second
 (what the method must read and write at least once, see `algorithmic_bytes`), to be read against
-the 8 TB/s HBM peak; ms per layer is reported beside it.
+the 8 TB/s HBM peak; ms per layer is reported beside it. The same run also measures, with a few steps
+each, the two other ways of calling the path (`modes`: LSE supplied by the caller, value-norm factor on),
+and for short shapes the step replayed from a HIP graph (`roofline.graph_replay`).
 
 Prints one JSON line. `--gpus N` with N > 1 is refused: this build is single-GPU.
 """
@@ -49,22 +51,53 @@ def scan_flops(w) -> float:
     return 2.0 * w.batch * w.n_q_heads * w.window * w.seq_len * w.head_dim
 
 
+def kernel_source_digest() -> str:
+    """sha256 over the HIP sources of the library (names and contents, in name order): what a counter summary under
+    profiles/ is stamped with, so that a summary taken before a kernel changed is not passed off as current."""
+    import hashlib
+
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_08686_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(kernel: str):
     """HBM bytes per launch of `kernel` on the C3 workload as measured with rocprofv3 counters
     (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size): read from the committed summary of
-    those runs, since counters cannot be collected from inside a timing run. None if not recorded."""
+    those runs, since counters cannot be collected from inside a timing run. None if not recorded, or
+    if the summary's stamp (`sources=`) is not the digest of the kernel sources this run uses."""
     path = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_c3.txt")
+    current, found = False, None
     try:
         for line in open(path):
             f = line.split()
+            if len(f) == 2 and f[0] == "stamp" and f[1] == "sources=" + kernel_source_digest():
+                current = True
             if len(f) == 4 and f[0] == "traffic" and f[1] == "kernel=" + kernel:
-                return int(f[2].split("=")[1]) + int(f[3].split("=")[1])
+                found = int(f[2].split("=")[1]) + int(f[3].split("=")[1])
     except OSError:
         pass
-    return None
+    return found if current else None
 
 
-def cpu_baseline(w, layer_t, tables, n_batch: int, value_norm: bool) -> dict:
+def host_cpu() -> dict:
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"model": model, "nproc": os.cpu_count()}
+
+
+def cpu_baseline(w, layer_t, tables, n_batch: int, value_norm: bool, single_thread: bool = False) -> dict:
     """Times the oracle (as it stands) on the first n_batch batch elements of layer 0."""
     import numpy as np
     import torch
@@ -87,10 +120,24 @@ def cpu_baseline(w, layer_t, tables, n_batch: int, value_norm: bool) -> dict:
     dt = time.perf_counter() - t0
     sub = w.scaled(batch=n_batch)
     nbytes = algorithmic_bytes(sub, int(out["count"].sum()), value_norm)
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"layer 0, batch elements 0..{n_batch - 1} of {w.batch} (all {w.n_kv_heads} KV heads), "
-                      f"whole chain, {dt:.2f} s",
-            "ms_per_layer_scaled": dt * 1e3 * w.batch / n_batch}
+    res = {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+           "sample": f"layer 0, batch elements 0..{n_batch - 1} of {w.batch} (all {w.n_kv_heads} KV heads), "
+                     f"whole chain, {dt:.2f} s",
+           "ms_per_layer_scaled": dt * 1e3 * w.batch / n_batch, "host": host_cpu()}
+    if single_thread:   # the small configurations: the same chain on one core
+        import subprocess
+        code = ("import sys, time, numpy as np; sys.path.insert(0, %r); import oracle; d = np.load(sys.argv[1]);"
+                "t0 = time.perf_counter();"
+                "oracle.window_scores(d['q'], d['k']); print(time.perf_counter() - t0)" % ROOT)
+        import tempfile
+        import numpy as np
+        with tempfile.NamedTemporaryFile(suffix=".npz") as f:
+            np.savez(f.name, q=qf, k=kf)
+            r = subprocess.run([sys.executable, "-c", code, f.name], capture_output=True, text=True,
+                               env=dict(os.environ, OMP_NUM_THREADS="1"))
+        if r.returncode == 0:
+            res["single_thread_scan_ms"] = float(r.stdout.strip().splitlines()[-1]) * 1e3
+    return res
 
 
 def layer_shared_bench(args, w, n_layers, torch, B, wl) -> int:
@@ -287,6 +334,9 @@ def main() -> int:
                          "alpha per prompt and one index set per layer (reported with the same metric). decode: the "
                          "decode-side consumer, one decoding query per head over every layer's compact cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-modes", action="store_true", help="skip the given-LSE and value-norm measurements")
+    ap.add_argument("--graph", action=argparse.BooleanOptionalAction, default=None,
+                    help="also time the step replayed from a HIP graph (default: for layers under 64 MiB)")
     ap.add_argument("--cpu-batch", type=int, default=0, help="batch elements in the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic for counter runs)")
@@ -319,35 +369,70 @@ def main() -> int:
     tables = wl.make_tables(w, dev)
     layers = [wl.make_layer(w, l % w.n_layers, dev) for l in range(n_layers)]
     q0, k0, v0 = layers[0]["q"], layers[0]["k"], layers[0]["v"]
-    params = [B.params_for(q0, k0, v0, pool=w.pool, pool_kernel=w.pool_kernel, budget=w.budget, cap=w.cap,
-                           layer=l % w.n_layers, n_layers=w.n_layers, flags=flags) for l in range(n_layers)]
-    buf = B.LayerBuffers(params[0], dev)
-    lse = None
-    if args.given_lse:
-        lse = [torch.empty(w.batch, w.n_q_heads, w.window, device=dev) for _ in range(n_layers)]
-        for l in range(n_layers):
-            B.ckv_window_lse(params[l], layers[l]["q"], layers[l]["k"], lse[l], buf.workspace)
-    torch.cuda.synchronize()
 
-    def step():
-        for l in range(n_layers):
-            t = layers[l]
-            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, buf, lse=None if lse is None else lse[l],
-                              fused_utility=not args.unfused)
+    def make_params(fl):
+        return [B.params_for(q0, k0, v0, pool=w.pool, pool_kernel=w.pool_kernel, budget=w.budget, cap=w.cap,
+                             layer=l % w.n_layers, n_layers=w.n_layers, flags=fl) for l in range(n_layers)]
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+    params = make_params(flags)
+    # every layer has its own outputs and scratch, like its own K and V
+    bufs = [B.LayerBuffers(params[l], dev) for l in range(n_layers)]
+    lse_all = None
+
+    def computed_lse():
+        nonlocal lse_all
+        if lse_all is None:
+            lse_all = [torch.empty(w.batch, w.n_q_heads, w.window, device=dev) for _ in range(n_layers)]
+            for l in range(n_layers):
+                B.ckv_window_lse(params[l], layers[l]["q"], layers[l]["k"], lse_all[l], bufs[l].workspace)
+            torch.cuda.synchronize()
+        return lse_all
+
+    def time_whole_pass(prm, lse, steps, warmup, fused=True):
+        """ms per step of the whole call sequence over all layers (wall clock around a synchronised region)."""
+        def step():
+            for l in range(n_layers):
+                t = layers[l]
+                B.retention_layer(prm[l], t["q"], t["k"], t["v"], tables, bufs[l], lse=None if lse is None else lse[l],
+                                  fused_utility=fused)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, step
+
+    lse = computed_lse() if args.given_lse else None
+    ms_per_step, step = time_whole_pass(params, lse, args.steps, args.warmup, fused=not args.unfused)
     ms_per_layer = ms_per_step / n_layers
-    kept = int(buf.count.sum().item())
+    kept = int(bufs[-1].count.sum().item())
     layer_bytes = algorithmic_bytes(w, kept, args.value_norm)
     value = layer_bytes / (ms_per_layer * 1e-3) / 1e9
+
+    # Short shapes are bound by the launches themselves (five per layer): the same step replayed from a HIP
+    # graph (the calls only launch kernels), every replay checked against the eager result.
+    graph_ms = None
+    if args.graph or (args.graph is None and layer_bytes < (64 << 20)):
+        ref = [(b_.idx.clone(), b_.count.clone(), b_.utility.clone()) for b_ in bufs]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        ok = True
+        for _ in range(max(args.warmup, 2)):
+            g.replay()
+            torch.cuda.synchronize()
+            ok = ok and all(torch.equal(b_.idx, r[0]) and torch.equal(b_.count, r[1]) and torch.equal(b_.utility, r[2])
+                            for b_, r in zip(bufs, ref))
+        if not ok:
+            print("bench.py: graph replay differs from the eager result", file=sys.stderr)
+            return 4
+        t0 = time.perf_counter()
+        for _ in range(args.steps * 10):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / (args.steps * 10) / n_layers
 
     # Per-kernel timing of the two scan passes with events on the launch stream (torch's current one).
     reps = max(2, min(args.steps, 5))
@@ -356,7 +441,7 @@ def main() -> int:
     pairs1, pairs2 = [], []
     for _ in range(reps):
         for l in range(n_layers):
-            t = layers[l]
+            t, buf = layers[l], bufs[l]
             a, b_, c = ev(), ev(), ev()
             a.record()
             B.ckv_window_lse(params[l], t["q"], t["k"], lse_buf, buf.workspace)
@@ -378,7 +463,7 @@ def main() -> int:
         marks[0].record()
         for l in range(n_layers):
             t = layers[l]
-            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, buf, lse=None if lse is None else lse[l],
+            B.retention_layer(params[l], t["q"], t["k"], t["v"], tables, bufs[l], lse=None if lse is None else lse[l],
                               fused_utility=not args.unfused)
             marks[l + 1].record()
         torch.cuda.synchronize()
@@ -389,7 +474,7 @@ def main() -> int:
     pairs3, pairs4 = [], []
     for _ in range(reps):
         for l in range(n_layers):
-            t = layers[l]
+            t, buf = layers[l], bufs[l]
             a, b_, c = ev(), ev(), ev()
             a.record()
             B.ckv_select_topk(params[l], buf.utility, buf.budget, buf.tau, buf.idx, buf.count, buf.workspace)
@@ -416,6 +501,10 @@ def main() -> int:
         dominant += " + vnorm_rows_kernel"   # timed together: K and V are each read once in that region
         dom_bytes += w.batch * w.n_kv_heads * w.seq_len * w.head_dim * (2 if bf16 else 4)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    # which bound the scan sits under: the matrix-core rate needed to keep up with the HBM peak is
+    # R = G * W flop per byte of K; the contraction is the bound where that exceeds what the kernels sustain
+    mfma1 = scan_flops(w) / (ms_pass1 * 1e-3) / 1e12
+    mfma2 = scan_flops(w) / (ms_pass2 * 1e-3) / 1e12
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -424,12 +513,42 @@ def main() -> int:
         "scan_ms": scan_ms,
         "select_ms": round(ms_select, 4), "gather_ms": round(ms_gather, 4),
         "gather_gbs": round(gather_bytes / (ms_gather * 1e-3) / 1e9, 1),
-        "mfma_tflops": {"rowstats": round(scan_flops(w) / (ms_pass1 * 1e-3) / 1e12, 1),
-                        "colsum": round(scan_flops(w) / (ms_pass2 * 1e-3) / 1e12, 1),  # fused: its fix-up kernel included
-                        "peak": MFMA_BF16_PEAK_TFLOPS},
+        "mfma_tflops": {"rowstats": round(mfma1, 1), "colsum": round(mfma2, 1),  # fused: its fix-up kernel included
+                        "peak": MFMA_BF16_PEAK_TFLOPS,
+                        "frac": round(max(mfma1, mfma2) / MFMA_BF16_PEAK_TFLOPS, 4) if bf16 else None},
         "whole_pass_frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "layer_ms": layer_ms,
     }
+    if graph_ms is not None:
+        roofline["graph_replay"] = {"ms_per_layer": round(graph_ms, 4),
+                                    "gbs": round(layer_bytes / (graph_ms * 1e-3) / 1e9, 1),
+                                    "frac_of_hbm_peak": round(layer_bytes / (graph_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # The other ways of calling the same path, measured in the same run with a few steps each: the caller
+    # supplies LSE (one pass over K), and the value-norm factor of Eq. 4 switched on (V read once more).
+    modes = None
+    if not args.no_modes and not args.given_lse and not args.value_norm and not args.unfused:
+        modes = {}
+        m_steps = max(2, min(args.steps, 3))
+        ms, _ = time_whole_pass(params, computed_lse(), m_steps, 1)
+        gbs = layer_bytes / (ms / n_layers * 1e-3) / 1e9
+        modes["given_lse"] = {"ms_per_layer": round(ms / n_layers, 4), "gbs": round(gbs, 1),
+                              "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "steps": m_steps,
+                              "algorithmic_bytes_per_layer": layer_bytes}
+        vparams = make_params(flags | B.FLAG_VALUE_NORM)
+        rho = torch.empty(w.batch, w.n_kv_heads, w.seq_len, device=dev)
+        for b_ in bufs:
+            b_.vnorm_ratio = rho   # one ratio buffer for all layers: 16 MiB that every layer overwrites
+        need = B.ckv_workspace_bytes(vparams[0])
+        if need > bufs[0].workspace.numel():
+            for b_ in bufs:
+                b_.workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        ms, _ = time_whole_pass(vparams, None, m_steps, 1)
+        vbytes = algorithmic_bytes(w, kept, True)
+        gbs = vbytes / (ms / n_layers * 1e-3) / 1e9
+        modes["value_norm"] = {"ms_per_layer": round(ms / n_layers, 4), "gbs": round(gbs, 1),
+                               "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "steps": m_steps,
+                               "algorithmic_bytes_per_layer": vbytes}
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -450,12 +569,16 @@ def main() -> int:
                    "budget_per_kv_head": w.budget, "pool": ["none", "avg", "max"][w.pool] + str(w.pool_kernel),
                    "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed",
                    "calls": ("window_scores+apply_tables" if args.unfused else "window_utility") + "+select_topk+compact_kv",
+                   "buffers": "every layer its own K, V, outputs and scratch",
                    "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
         "roofline": roofline,
     }
+    if modes is not None:
+        out["modes"] = modes
     if not args.no_cpu_baseline:
         nb = args.cpu_batch or w.batch
-        out["cpu_baseline"] = cpu_baseline(w, layers[0], tables, nb, args.value_norm)
+        out["cpu_baseline"] = cpu_baseline(w, layers[0], tables, nb, args.value_norm,
+                                           single_thread=args.config in ("c1", "c2"))
     print(json.dumps(out))
     return 0
 
