@@ -54,5 +54,22 @@ def build_library(verbose: bool = False) -> Path:
     return LIB
 
 
+def build_probes() -> list:
+    """Compile the measurement probes under probes/ (stand-alone HIP programs; not part of the library)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    probes = PKG / "probes"
+    subprocess.run([sys.executable, str(probes / "issue_patterns.py")], check=True)
+    out = []
+    for name in ("read_bandwidth", "issue_patterns"):
+        exe = probes / name
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-w", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", str(probes / (name + ".hip")), "-o", str(exe)], check=True)
+        out.append(exe)
+    return out
+
+
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    if len(sys.argv) > 1 and sys.argv[1] == "probes":
+        print(*build_probes(), sep="\n")
+    else:
+        print(build_library(verbose=True))

@@ -1119,6 +1119,12 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
   hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
 }
 
+// Up to this many workgroups along the key axis, the second pass merges the first pass's row partials in
+// its own prologue (every workgroup of a unit repeats the merge, which is cheaper than a launch while the
+// partials are few); beyond it the small merge kernel runs in between (measured at 32 partials per row,
+// T = 128k with 8 units: 26 us of prologue against 11 us for the kernel).
+constexpr int kMergeInPassTwo = 4;
+
 // Launches for the query-tile counts NQ_LO..NQ_HI (the instantiations are spread over several translation
 // units, each covering a range, to keep compile times apart).
 template <int DT, int DH, int NQ_LO, int NQ_HI>
@@ -1128,7 +1134,8 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, b
 #define CKV_LAUNCH_NQ(NQ)                                                          \
   case NQ:                                                                         \
     if constexpr (NQ >= NQ_LO && NQ <= NQ_HI) {                                    \
-      a.lse_from_part = need_lse && need_scores && colsum_is_staged<DT, NQ>(s);    \
+      a.lse_from_part = need_lse && need_scores && colsum_is_staged<DT, NQ>(s) && \
+                        s.n_chunks <= kMergeInPassTwo;                              \
       if (need_lse) launch_rowstats<DT, DH, NQ>(s, a, grid, block, stream);        \
       if (need_scores) launch_colsum<DT, DH, NQ>(s, a, grid, block, stream);       \
       break;                                                                       \
