@@ -1119,11 +1119,12 @@ static void launch_colsum(const Shape &s, const ScoreArgs &a, dim3 grid, dim3 bl
   hipLaunchKernelGGL((colsum_kernel<DT, DH, NQ>), grid, block, 0, stream, a);
 }
 
-// Up to this many workgroups along the key axis, the second pass merges the first pass's row partials in
-// its own prologue (every workgroup of a unit repeats the merge, which is cheaper than a launch while the
-// partials are few); beyond it the small merge kernel runs in between (measured at 32 partials per row,
-// T = 128k with 8 units: 26 us of prologue against 11 us for the kernel).
-constexpr int kMergeInPassTwo = 4;
+// Where a lane has at most this many row partials to merge (query tiles per wave x workgroups along the key
+// axis), the second pass merges the first pass's partials in its own prologue: every workgroup of a unit
+// repeats the merge, which is cheaper than a launch while the partials are few. Beyond it the small merge
+// kernel runs in between (measured at 8 tiles x 32 workgroups, T = 128k with 8 units: 26 us of prologue
+// against 11 us for the kernel; at 4 x 8 the kernel still wins, at 4 x 2 and 1 x 8 the prologue does).
+constexpr int kMergeInPassTwo = 16;
 
 // Launches for the query-tile counts NQ_LO..NQ_HI (the instantiations are spread over several translation
 // units, each covering a range, to keep compile times apart).
@@ -1135,7 +1136,7 @@ static hipError_t launch_scores_t(const Shape &s, ScoreArgs &a, bool need_lse, b
   case NQ:                                                                         \
     if constexpr (NQ >= NQ_LO && NQ <= NQ_HI) {                                    \
       a.lse_from_part = need_lse && need_scores && colsum_is_staged<DT, NQ>(s) && \
-                        s.n_chunks <= kMergeInPassTwo;                              \
+                        NQ * s.n_chunks <= kMergeInPassTwo;                         \
       if (need_lse) launch_rowstats<DT, DH, NQ>(s, a, grid, block, stream);        \
       if (need_scores) launch_colsum<DT, DH, NQ>(s, a, grid, block, stream);       \
       break;                                                                       \
