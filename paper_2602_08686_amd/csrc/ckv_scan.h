@@ -516,6 +516,9 @@ __device__ __forceinline__ WaveRange wave_range(const ScoreArgs &a, const BlockC
 }
 
 // Everything the two staged kernels share: the ring, the per-lane offsets, Q in registers.
+#ifndef CKV_PIN_Q_ABOVE
+#define CKV_PIN_Q_ABOVE 4
+#endif
 template <int DT, int DH, int NQ>
 struct Staged {
   using G = Geom<DT, DH>;
@@ -586,6 +589,14 @@ struct Staged {
       if (!valid) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) qf[i][c] = chunk_t{0u, 0u, 0u, 0u};
+      }
+      // With more than four query tiles the ordinary vector registers are what runs out (the logits, the key
+      // tile and the vector work's temporaries must live there), while the matrix cores take their operands
+      // from accumulation registers just as well: say where Q is to live, or the allocator keeps a tile of it
+      // in vector registers and serialises the exponentials through one temporary.
+      if constexpr (NQ > CKV_PIN_Q_ABOVE) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) asm volatile("" : "+a"(qf[i][c]));
       }
     }
     __syncthreads();  // the images that held Q are free for key tiles from here on
