@@ -502,6 +502,17 @@ __device__ __forceinline__ void interleave_hint() {
 __host__ __device__ constexpr int unroll_tiles(int nq) { return nq > 4 ? 2 : kRing; }
 static_assert(kRing % 2 == 0, "half a ring cycle starts at an even image");
 
+// Vector instructions that the hint places behind each MFMA of the next pair's chain. Fewer than an even
+// spread (pass 1 has ~63 per 8 MFMAs, pass 2 ~52 per 9): the chain is then issued early, and what is left
+// of the current pair's vector work runs after its last MFMA -- the 18 wait states between an MFMA and the
+// first read of its result are filled with work instead of s_nop (one `s_nop 11` per pair with an even
+// spread). Measured in cycles per pair where memory does not limit (T = 128k, W = 64, eight tiles per
+// wave): pass 1 492 (8 per MFMA), 426 (6), 439 (5); pass 2 517 (6), 492 (5), 428 (4), 443 (3). With
+// four tiles per wave on the 32k / batch-16 shape, which sits at the memory ceiling, pass 1 gains 3 us with
+// 6 and pass 2 is best left at 6 (5 and 4: 2-3 us slower).
+__host__ __device__ constexpr int vector_per_mfma_pass1(int nq) { return 6; }
+__host__ __device__ constexpr int vector_per_mfma_pass2(int nq) { return nq > 4 ? 4 : 6; }
+
 // Geometry of a wave's key range: wave-uniform values live in scalar registers.
 struct WaveRange {
   int wave, t_begin, t_end, n_full;
@@ -663,8 +674,8 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) rowstats_lds_kernel(ScoreA
         if (i + 1 < NQ) mma_chain<DT, NCH>(acc[cur ^ 1], kreg[v & 1], qf[i + 1]);
         else mma_chain<DT, NCH>(acc[cur ^ 1], kreg[(v + 1) & 1], qf[0]);
         rowstats_update<false>(acc[cur], a.c2, 0, hh, 0, rm[i], rl[i]);
-        if (i == READ_AT) interleave_hint<N_MFMA, 8, NCH>();
-        else interleave_hint<N_MFMA, 8, 0>();
+        if (i == READ_AT) interleave_hint<N_MFMA, vector_per_mfma_pass1(NQ), NCH>();
+        else interleave_hint<N_MFMA, vector_per_mfma_pass1(NQ), 0>();
       }
       st.kcur += st.tile_stride;
     }
@@ -1041,8 +1052,8 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
           bias[0].add(acc[cur ^ 1], ones);
         }
         cs[i] = colsum_weights<false>(acc[cur], a.c2, hh, 0);
-        if (i == READ_AT) interleave_hint<N_MFMA, 6, NCH>();
-        else interleave_hint<N_MFMA, 6, 0>();
+        if (i == READ_AT) interleave_hint<N_MFMA, vector_per_mfma_pass2(NQ), NCH>();
+        else interleave_hint<N_MFMA, vector_per_mfma_pass2(NQ), 0>();
       }
       if constexpr (UTIL) stage_column_sums<NQ, WT, kUtilRow>(cs, a.norm, stage + kUtilCarry, u, m, hh);
       else stage_column_sums<NQ, WT>(cs, a.norm, stage, u, m, hh);
