@@ -16,7 +16,10 @@ constexpr int kMaxQTiles = 8;      // query-row tiles a wave keeps in registers 
 constexpr int kMaxQTilesF32 = 4;
 constexpr int kMaxWindowTiles = 4; // 32-row tiles per query head: W <= 128
 constexpr int kScoreWaves = 4;     // waves per workgroup in the scan kernels
-constexpr int kComputeUnits = 256; // MI355X
+// Compute units of the build target (gfx950: MI355X, 256). A constant on purpose, not a device query: the
+// split of the key axis, and with it the workspace layout, must be the same for ckv_workspace_bytes
+// (which may run where no device is visible) and for the calls that use the workspace.
+constexpr int kComputeUnits = 256;
 constexpr int kSelectThreads = 1024;
 // Geometry of the fused utility form of the scan's second pass, shared by that pass (ckv_scan.h) and by
 // the kernel that finishes what it leaves out (ckv_tables.hip). The pass works in rounds of
