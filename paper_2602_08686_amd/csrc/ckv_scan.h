@@ -680,15 +680,22 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) rowstats_lds_kernel(ScoreA
       st.kcur += st.tile_stride;
     }
   }
+  // What the pipeline left: up to a ring of whole tiles and the masked ones. Their loads go out a ring at
+  // a time, so the memory latency is paid once per ring and not once per tile.
   wait_vm<0>();
-  for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
-    dma_tile_clamped<G>(st.kbase, a.ks_t, t0, a.T, lane, ring[wr.wave][0]);
-    wait_vm<0>();
-    read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
+  for (int r0 = wr.t_begin + n_piped * kTile; r0 < wr.t_end; r0 += kRing * kTile) {
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      mma_chain<DT, NCH>(acc[0], kreg[0], qf[i]);
-      rowstats_update<true>(acc[0], a.c2, t0, hh, limit[i], rm[i], rl[i]);
+    for (int j = 0; j < kRing; ++j)
+      if (r0 + j * kTile < wr.t_end) dma_tile_clamped<G>(st.kbase, a.ks_t, r0 + j * kTile, a.T, lane, ring[wr.wave][j]);
+    wait_vm<0>();
+    for (int j = 0; j < kRing && r0 + j * kTile < wr.t_end; ++j) {
+      const int t0 = r0 + j * kTile;
+      read_image<G>(kreg[0], ring[wr.wave][j], st.roff);
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        mma_chain<DT, NCH>(acc[0], kreg[0], qf[i]);
+        rowstats_update<true>(acc[0], a.c2, t0, hh, limit[i], rm[i], rl[i]);
+      }
     }
   }
   store_row_partials<NQ>(a, bc, wr.wave, m, hh, rm, rl);
@@ -1068,21 +1075,26 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
     }
   }
   wait_vm<0>();
-  for (int t0 = wr.t_begin + n_piped * kTile; t0 < wr.t_end; t0 += kTile) {
-    dma_tile_clamped<G>(st.kbase, a.ks_t, t0, a.T, lane, ring[wr.wave][0]);
-    wait_vm<0>();
-    read_image<G>(kreg[0], ring[wr.wave][0], st.roff);
-    const int kt = t0 + m;
-    float cs[NQ];
+  for (int r0 = wr.t_begin + n_piped * kTile; r0 < wr.t_end; r0 += kRing * kTile) {  // loads a ring at a time
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      const int j0 = ((bc.grp * NQ + i) % WT) * kTile;
-      mma_chain<DT, NCH>(acc[0], qf[i], kreg[0]);
-      bias[i].add(acc[0], ones);
-      cs[i] = colsum_weights<true>(acc[0], a.c2, hh, kt - a.P - j0);
+    for (int j = 0; j < kRing; ++j)
+      if (r0 + j * kTile < wr.t_end) dma_tile_clamped<G>(st.kbase, a.ks_t, r0 + j * kTile, a.T, lane, ring[wr.wave][j]);
+    wait_vm<0>();
+    for (int j = 0; j < kRing && r0 + j * kTile < wr.t_end; ++j) {
+      const int t0 = r0 + j * kTile;
+      read_image<G>(kreg[0], ring[wr.wave][j], st.roff);
+      const int kt = t0 + m;
+      float cs[NQ];
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        const int j0 = ((bc.grp * NQ + i) % WT) * kTile;
+        mma_chain<DT, NCH>(acc[0], qf[i], kreg[0]);
+        bias[i].add(acc[0], ones);
+        cs[i] = colsum_weights<true>(acc[0], a.c2, hh, kt - a.P - j0);
+      }
+      if constexpr (GSUM) store_group_sum<NQ>(a, bc, cs, kt, hh);
+      else store_column_sums<NQ>(a, bc, cs, WT, kt, hh);
     }
-    if constexpr (GSUM) store_group_sum<NQ>(a, bc, cs, kt, hh);
-    else store_column_sums<NQ>(a, bc, cs, WT, kt, hh);
   }
 }
 
