@@ -2,8 +2,10 @@
 """Benchmark of the prefill-end retention step (window scan + tables + select + gather) on one MI355X.
 
 A step is one pass of the whole hot path over every layer of one synthetic prompt batch: for each
-layer the C-ABI calls are queued back-to-back on one stream, every layer with its own K/V, output and
-scratch buffers already resident in HBM. The headline value is algorithmic bytes moved per second
+layer the C-ABI calls are queued back-to-back on a stream, every layer with its own K/V, output and
+scratch buffers already resident in HBM. The layers of a step are dealt to `--streams` HIP streams in turn
+(default 2; they are independent, so one layer's short kernels overlap the next layer's scan); the same
+steps on a single stream are timed in the same run (`one_stream`). The headline value is algorithmic bytes moved per second
 (what the method must read and write at least once, see `algorithmic_bytes`), to be read against
 the 8 TB/s HBM peak; ms per layer is reported beside it. The same run also measures, with a few steps
 each, the two other ways of calling the path (`modes`: LSE supplied by the caller, value-norm factor on),
@@ -333,6 +335,8 @@ def main() -> int:
                     help="per_head: the north-star path (default). layer_shared: the paper's Alg. 1 as printed, one "
                          "alpha per prompt and one index set per layer (reported with the same metric). decode: the "
                          "decode-side consumer, one decoding query per head over every layer's compact cache")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams the layers of a step are dealt to in turn (1: every layer behind the previous one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-modes", action="store_true", help="skip the given-LSE and value-norm measurements")
     ap.add_argument("--graph", action=argparse.BooleanOptionalAction, default=None,
@@ -388,13 +392,21 @@ def main() -> int:
             torch.cuda.synchronize()
         return lse_all
 
-    def time_whole_pass(prm, lse, steps, warmup, fused=True):
-        """ms per step of the whole call sequence over all layers (wall clock around a synchronised region)."""
+    # Layers are independent of one another (each has its K, V, outputs and scratch), so a caller that compacts
+    # a whole model at the end of prefill can queue them on more than one stream: the short, latency-bound
+    # kernels of one layer (selection, fix-up, gather) and the ends of its scans then overlap the next layer's
+    # scan. All streams have the default priority.
+    side_streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
+
+    def time_whole_pass(prm, lse, steps, warmup, fused=True, streams=None):
+        """ms per step of the whole call sequence over all layers (wall clock around a synchronised region);
+        layer l goes to streams[l % len(streams)], or all to the current stream."""
         def step():
             for l in range(n_layers):
                 t = layers[l]
+                st = None if streams is None else streams[l % len(streams)]
                 B.retention_layer(prm[l], t["q"], t["k"], t["v"], tables, bufs[l], lse=None if lse is None else lse[l],
-                                  fused_utility=fused)
+                                  stream=st, fused_utility=fused)
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
@@ -405,8 +417,12 @@ def main() -> int:
         return (time.perf_counter() - t0) * 1e3 / steps, step
 
     lse = computed_lse() if args.given_lse else None
-    ms_per_step, step = time_whole_pass(params, lse, args.steps, args.warmup, fused=not args.unfused)
+    ms_per_step, _ = time_whole_pass(params, lse, args.steps, args.warmup, fused=not args.unfused, streams=side_streams)
     ms_per_layer = ms_per_step / n_layers
+    # the same steps on one stream: every kernel of a layer behind the previous layer's last
+    one_stream_ms, step = time_whole_pass(params, lse, args.steps, 1, fused=not args.unfused)
+    if side_streams is None:
+        one_stream_ms = ms_per_step
     kept = int(bufs[-1].count.sum().item())
     layer_bytes = algorithmic_bytes(w, kept, args.value_norm)
     value = layer_bytes / (ms_per_layer * 1e-3) / 1e9
@@ -530,20 +546,21 @@ def main() -> int:
     if not args.no_modes and not args.given_lse and not args.value_norm and not args.unfused:
         modes = {}
         m_steps = max(2, min(args.steps, 3))
-        ms, _ = time_whole_pass(params, computed_lse(), m_steps, 1)
+        ms, _ = time_whole_pass(params, computed_lse(), m_steps, 1, streams=side_streams)
         gbs = layer_bytes / (ms / n_layers * 1e-3) / 1e9
         modes["given_lse"] = {"ms_per_layer": round(ms / n_layers, 4), "gbs": round(gbs, 1),
                               "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "steps": m_steps,
                               "algorithmic_bytes_per_layer": layer_bytes}
         vparams = make_params(flags | B.FLAG_VALUE_NORM)
-        rho = torch.empty(w.batch, w.n_kv_heads, w.seq_len, device=dev)
-        for b_ in bufs:
-            b_.vnorm_ratio = rho   # one ratio buffer for all layers: 16 MiB that every layer overwrites
+        # one ratio buffer per stream (16 MiB that every layer on that stream overwrites)
+        rho = [torch.empty(w.batch, w.n_kv_heads, w.seq_len, device=dev) for _ in range(max(args.streams, 1))]
+        for l, b_ in enumerate(bufs):
+            b_.vnorm_ratio = rho[l % len(rho)]
         need = B.ckv_workspace_bytes(vparams[0])
         if need > bufs[0].workspace.numel():
             for b_ in bufs:
                 b_.workspace = torch.empty(need, dtype=torch.uint8, device=dev)
-        ms, _ = time_whole_pass(vparams, None, m_steps, 1)
+        ms, _ = time_whole_pass(vparams, None, m_steps, 1, streams=side_streams)
         vbytes = algorithmic_bytes(w, kept, True)
         gbs = vbytes / (ms / n_layers * 1e-3) / 1e9
         modes["value_norm"] = {"ms_per_layer": round(ms / n_layers, 4), "gbs": round(gbs, 1),
@@ -570,8 +587,11 @@ def main() -> int:
                    "value_norm": bool(args.value_norm), "lse": "given" if args.given_lse else "computed",
                    "calls": ("window_scores+apply_tables" if args.unfused else "window_utility") + "+select_topk+compact_kv",
                    "buffers": "every layer its own K, V, outputs and scratch",
+                   "streams": max(args.streams, 1),
                    "algorithmic_bytes_per_layer": layer_bytes, "kept_rows_last_layer": kept},
         "roofline": roofline,
+        "one_stream": {"ms_per_layer": round(one_stream_ms / n_layers, 4),
+                       "gbs": round(layer_bytes / (one_stream_ms / n_layers * 1e-3) / 1e9, 1)},
     }
     if modes is not None:
         out["modes"] = modes
