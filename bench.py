@@ -417,12 +417,11 @@ def main() -> int:
         return (time.perf_counter() - t0) * 1e3 / steps, step
 
     lse = computed_lse() if args.given_lse else None
-    ms_per_step, _ = time_whole_pass(params, lse, args.steps, args.warmup, fused=not args.unfused, streams=side_streams)
+    ms_per_step, step = time_whole_pass(params, lse, args.steps, args.warmup, fused=not args.unfused, streams=side_streams)
     ms_per_layer = ms_per_step / n_layers
-    # the same steps on one stream: every kernel of a layer behind the previous layer's last
-    one_stream_ms, step = time_whole_pass(params, lse, args.steps, 1, fused=not args.unfused)
-    if side_streams is None:
-        one_stream_ms = ms_per_step
+    one_stream_ms = ms_per_step
+    if side_streams is not None:  # the same steps on one stream: every kernel of a layer behind the previous layer's last
+        one_stream_ms, step = time_whole_pass(params, lse, args.steps, 1, fused=not args.unfused)
     kept = int(bufs[-1].count.sum().item())
     layer_bytes = algorithmic_bytes(w, kept, args.value_norm)
     value = layer_bytes / (ms_per_layer * 1e-3) / 1e9
