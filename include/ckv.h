@@ -25,6 +25,9 @@
  *   - every call only enqueues work on `hip_stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and returns; outputs are valid once the stream reaches that point;
  *   - inputs are never written; outputs must not alias inputs or each other;
+ *   - calls may be queued on different streams (and from different host threads) and overlap on the
+ *     GPU as long as they share no output and no workspace: give every stream a workspace of its own
+ *     (ckv_window_lse_static, whose scratch is the library's, is the exception: see there);
  *   - arguments are validated on the host BEFORE anything is launched: on any error nothing has
  *     been enqueued and the status says why (ckv_status_string gives text);
  *   - tensors are dense row-major in the order written in their comment, except Q/K/V which carry
