@@ -462,7 +462,8 @@ def main() -> int:
             B.ckv_window_lse(params[l], t["q"], t["k"], lse_buf, buf.workspace)
             b_.record()
             if args.unfused:
-                B.ckv_window_scores(params[l], t["q"], t["k"], None, lse_buf, buf.scores, None, buf.workspace)
+                B.ckv_window_scores(params[l], t["q"], t["k"], t["v"] if args.value_norm else None, lse_buf, buf.scores,
+                                    buf.vnorm_ratio, buf.workspace)
             else:  # second pass with pooling, weights and group maximum on chip, plus its edge fix-up kernel
                 B.ckv_window_utility(params[l], t["q"], t["k"], t["v"] if args.value_norm else None, lse_buf,
                                      tables["w_head"], tables.get("head_share"), tables.get("t_gate"),
@@ -508,9 +509,9 @@ def main() -> int:
     dominant, dom_ms = ((("rowstats_lds_kernel" if bf16 else "rowstats_kernel"), ms_pass1)
                         if ms_pass1 >= ms_pass2 and not args.given_lse
                         else (("colsum_lds_kernel" if bf16 else "colsum_kernel"), ms_pass2))
-    pass2_has_v = args.value_norm and not args.unfused  # the fused call also reads V for the value norms
+    pass2_has_v = args.value_norm  # the second call also reads V for the value norms
     scan_ms = {"rowstats+lse": round(ms_pass1, 4),
-               ("colsum" if args.unfused else "colsum+tables+vnorm" if pass2_has_v else "colsum+tables"): round(ms_pass2, 4)}
+               ("colsum" if args.unfused else "colsum+tables") + ("+vnorm" if pass2_has_v else ""): round(ms_pass2, 4)}
     dom_bytes = scan_bytes(w)
     if pass2_has_v and dominant.startswith("colsum"):
         dominant += " + vnorm_rows_kernel"   # timed together: K and V are each read once in that region
