@@ -813,6 +813,11 @@ __device__ __forceinline__ void stage_column_sums(const float (&cs)[NQ], float n
   }
 }
 
+// The stage is written by one set of lanes and read by another of the same wave. The hardware keeps a
+// wave's LDS operations in order, but the compiler, reasoning per lane, sees a store and a load that can
+// never touch the same word and may swap them: this keeps every memory access on its side of the line.
+__device__ __forceinline__ void stage_fence() { asm volatile("" ::: "memory"); }
+
 template <int NQ, int WT>
 __device__ __forceinline__ void flush_column_sums(const ScoreArgs &a, const BlockCoord &bc, const float *stage,
                                                   int t_first, int lane, __amdgpu_buffer_rsrc_t rsrc) {
@@ -865,76 +870,106 @@ __device__ __forceinline__ void flush_group_sums(const ScoreArgs &a, const Block
 // ends up with the group maximum of two adjacent keys and stores them with one 64-bit store. The taps
 // are combined left to right, as the stand-alone tables kernel does.
 constexpr int kUtilRow = kUtilCarry + kRing * kTile;
+// win[hp]: the twelve values around this lane's four keys (win[hp][4 .. 7]) of head 2 hp + half.
 template <int NH, int POOL, int R>
-__device__ __forceinline__ void pooled_group_max(const ScoreArgs &a, const float *rows, int lane, int heads_left,
-                                                 const float (&wgt)[NH], float (&best)[4]) {
-  const int half = lane >> 5, grp = lane & 31;  // keys 4 grp - 32 .. 4 grp - 29 of the block
+__device__ __forceinline__ void pooled_group_max(const ScoreArgs &a, const float (&win)[(NH + 1) / 2][12], int lane,
+                                                 int heads_left, const float (&wgt)[NH], float (&best)[4]) {
+  const int half = lane >> 5;
 #pragma unroll
   for (int e = 0; e < 4; ++e) best[e] = -INFINITY;
 #pragma unroll
   for (int hp = 0; hp < (NH + 1) / 2; ++hp) {
     const int h = 2 * hp + half;
-    if (2 * hp >= heads_left) break;
     const bool live = h < NH && h < heads_left;
-    const float *row = rows + (live ? h : 0) * kUtilRow + (kUtilCarry - kUtilShift - 4) + 4 * grp;  // row[4 .. 7]: this lane's keys
-    float w[12];
-#pragma unroll
-    for (int q = 0; q < 3; ++q) {
-      const f32x4 v = *reinterpret_cast<const f32x4 *>(row + 4 * q);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) w[4 * q + e] = v[e];
-    }
     float wg = 0.0f;
 #pragma unroll
     for (int x = 0; x < NH; ++x) wg = (x == h) ? wgt[x] : wg;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float c = w[4 + e - R];
+      float c = win[hp][4 + e - R];
 #pragma unroll
-      for (int d = 1 - R; d <= R; ++d) c = POOL == CKV_POOL_MAX ? fmaxf(c, w[4 + e + d]) : c + w[4 + e + d];
+      for (int d = 1 - R; d <= R; ++d) c = POOL == CKV_POOL_MAX ? fmaxf(c, win[hp][4 + e + d]) : c + win[hp][4 + e + d];
       if (POOL == CKV_POOL_AVG) c *= a.inv_kernel;
-      best[e] = live ? fmaxf(best[e], wg * c) : best[e];
+      // a select, not a branch: heads that do not exist leave the maximum alone
+      best[e] = fmaxf(best[e], live ? wg * c : -INFINITY);
     }
   }
 }
 
-// rows: the wave's stage rows (carry included); t_first: first key of the block just staged.
+// rows: the wave's stage rows (carry included); t_first: first key of the block just staged. Every LDS
+// read of the flush is issued before anything waits for one (the wave is alone on its SIMD: a read's
+// latency is otherwise paid once per dependent step).
 template <int NQ, int WT>
 __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoord &bc, float *rows, int t_first,
                                               bool first_block, bool last_block, int lane,
                                               __amdgpu_buffer_rsrc_t rsrc, __amdgpu_buffer_rsrc_t rsrc_u,
                                               const float (&wgt)[NQ / WT]) {
   constexpr int NH = NQ / WT;
+  constexpr int NP = (NH + 1) / 2;  // pairs of heads: lanes 0..31 take the even head, lanes 32..63 the odd one
   constexpr int BLK = kRing * kTile;
   const int head0 = bc.g * a.G + (bc.grp * NQ) / WT;
   const int heads_left = a.G - (bc.grp * NQ) / WT;
+  const int half = lane >> 5, grp = lane & 31, key4 = 4 * grp;
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
   typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
   typedef __attribute__((ext_vector_type(2))) float f32x2;
-  // raw column sums for the fix-up kernel: the first block's first eight keys, the last block's last eight
+  // -- reads: raw sums of this lane's keys, the pooling windows, the pieces of the carry
+  f32x4 raw[NP];
+  float win[NP][12];
 #pragma unroll
-  for (int h = 0; h < NH; h += 2) {
-    const int mine = h + (lane >> 5), key4 = 4 * (lane & 31);
+  for (int hp = 0; hp < NP; ++hp) {
+    const int mine = 2 * hp + half;
+    const float *row = rows + (mine < NH ? mine : 0) * kUtilRow;
+    raw[hp] = *reinterpret_cast<const f32x4 *>(row + kUtilCarry + key4);
+    const float *w0 = row + (kUtilCarry - kUtilShift - 4) + key4;  // w0[4 .. 7]: keys 4 grp - 32 .. of the block
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(w0 + 4 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) win[hp][4 * q + e] = v[e];
+    }
+  }
+  constexpr int PER = kUtilCarry / 4;  // 128-bit pieces of the carry per head
+  constexpr int NC = (PER * NH + kWave - 1) / kWave;
+  static_assert(NC <= 2, "at most two pieces per lane");
+  f32x4 carry[NC];
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int piece = lane + i * kWave;
+    const int pc = piece < PER * NH ? piece : 0;
+    carry[i] = *reinterpret_cast<const f32x4 *>(rows + (pc / PER) * kUtilRow + BLK + 4 * (pc % PER));
+  }
+  // -- carry: the block's last kUtilCarry values move in front of the rows for the next block (LDS operations
+  // of a wave complete in order: the windows above were read before these writes land)
+  stage_fence();
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int piece = lane + i * kWave;
+    if (piece < PER * NH) *reinterpret_cast<f32x4 *>(rows + (piece / PER) * kUtilRow + 4 * (piece % PER)) = carry[i];
+  }
+  // -- raw column sums for the fix-up kernel: the first block's first eight keys, the last block's last 40
+#pragma unroll
+  for (int hp = 0; hp < NP; ++hp) {
+    const int mine = 2 * hp + half;
     const bool valid = mine < NH && mine < heads_left &&
                        ((first_block && key4 < kUtilHead) || (last_block && key4 >= BLK - kUtilCarry));
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(rows + (mine < NH ? mine : 0) * kUtilRow + kUtilCarry + key4);
     const uint32_t off = valid ? (uint32_t)(((head0 + mine) * a.T + t_first + key4) * 4) : 0x80000000u;
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, off, 0, kOutStoreAux);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, raw[hp]), rsrc, off, 0, kOutStoreAux);
   }
   float best[4];
   if (a.pool == CKV_POOL_MAX) {
     switch (a.radius) {
-      case 1: pooled_group_max<NH, CKV_POOL_MAX, 1>(a, rows, lane, heads_left, wgt, best); break;
-      case 2: pooled_group_max<NH, CKV_POOL_MAX, 2>(a, rows, lane, heads_left, wgt, best); break;
-      case 3: pooled_group_max<NH, CKV_POOL_MAX, 3>(a, rows, lane, heads_left, wgt, best); break;
-      default: pooled_group_max<NH, CKV_POOL_MAX, 0>(a, rows, lane, heads_left, wgt, best); break;
+      case 1: pooled_group_max<NH, CKV_POOL_MAX, 1>(a, win, lane, heads_left, wgt, best); break;
+      case 2: pooled_group_max<NH, CKV_POOL_MAX, 2>(a, win, lane, heads_left, wgt, best); break;
+      case 3: pooled_group_max<NH, CKV_POOL_MAX, 3>(a, win, lane, heads_left, wgt, best); break;
+      default: pooled_group_max<NH, CKV_POOL_MAX, 0>(a, win, lane, heads_left, wgt, best); break;
     }
   } else {
     switch (a.radius) {
-      case 1: pooled_group_max<NH, CKV_POOL_AVG, 1>(a, rows, lane, heads_left, wgt, best); break;
-      case 2: pooled_group_max<NH, CKV_POOL_AVG, 2>(a, rows, lane, heads_left, wgt, best); break;
-      case 3: pooled_group_max<NH, CKV_POOL_AVG, 3>(a, rows, lane, heads_left, wgt, best); break;
-      default: pooled_group_max<NH, CKV_POOL_AVG, 0>(a, rows, lane, heads_left, wgt, best); break;
+      case 1: pooled_group_max<NH, CKV_POOL_AVG, 1>(a, win, lane, heads_left, wgt, best); break;
+      case 2: pooled_group_max<NH, CKV_POOL_AVG, 2>(a, win, lane, heads_left, wgt, best); break;
+      case 3: pooled_group_max<NH, CKV_POOL_AVG, 3>(a, win, lane, heads_left, wgt, best); break;
+      default: pooled_group_max<NH, CKV_POOL_AVG, 0>(a, win, lane, heads_left, wgt, best); break;
     }
   }
   // (x, y) -> ([x.lo, y.lo], [x.hi, y.hi]): lanes 0..31 get both halves' values of keys 0 and 1 of their
@@ -943,22 +978,12 @@ __device__ __forceinline__ void flush_utility(const ScoreArgs &a, const BlockCoo
   const auto s13 = __builtin_amdgcn_permlane32_swap(__float_as_uint(best[1]), __float_as_uint(best[3]), false, false);
   const f32x2 out = {fmaxf(__uint_as_float(s02[0]), __uint_as_float(s02[1])),
                      fmaxf(__uint_as_float(s13[0]), __uint_as_float(s13[1]))};
-  const int grp = lane & 31;
   // groups 0..7 lie in front of the block; in the range's first block they and group 8 (the range's
   // first four keys, whose windows reach in front of the range) are left to the fix-up kernel
   const bool emit = grp >= kUtilShift / 4 + 1 || !first_block;
   const uint32_t off_u =
-      emit ? (uint32_t)((bc.g * a.P + t_first - kUtilShift + 4 * grp + 2 * (lane >> 5)) * 4) : 0x80000000u;
+      emit ? (uint32_t)((bc.g * a.P + t_first - kUtilShift + 4 * grp + 2 * half) * 4) : 0x80000000u;
   __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, out), rsrc_u, off_u, 0, kOutStoreAux);
-  // carry: the block's last kUtilCarry values move in front of the rows for the next block
-  constexpr int PER = kUtilCarry / 4;  // 128-bit pieces per head
-  static_assert(PER * NH <= 2 * kWave, "at most two pieces per lane");
-#pragma unroll
-  for (int piece = lane; piece < PER * NH; piece += kWave) {
-    float *row = rows + (piece / PER) * kUtilRow;
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(row + BLK + 4 * (piece % PER));
-    *reinterpret_cast<f32x4 *>(row + 4 * (piece % PER)) = v;
-  }
 }
 
 template <int DT, int DH, int NQ, int WT, bool UTIL = false, bool GSUM = false>
@@ -1068,10 +1093,12 @@ __global__ void __launch_bounds__(kScoreWaves *kWave) colsum_lds_kernel(ScoreArg
     }
     if (UR == kRing || slot0 + UR == kRing) {  // a ring cycle is complete
       const int c0 = t0 + UR - kRing;          // its first tile
+      stage_fence();  // the tiles' sums are staged
       if constexpr (UTIL)
         flush_utility<NQ, WT>(a, bc, stage, wr.t_begin + c0 * kTile, c0 == 0, c0 + kRing >= n_piped, lane, rsrc, rsrc_u, wgt);
       else if constexpr (GSUM) flush_group_sums<NQ>(a, bc, stage, wr.t_begin + c0 * kTile, lane, rsrc);
       else flush_column_sums<NQ, WT>(a, bc, stage, wr.t_begin + c0 * kTile, lane, rsrc);
+      stage_fence();  // and read, before the next cycle's overwrite them
     }
   }
   wait_vm<0>();
