@@ -1,16 +1,17 @@
 // Kernel templates of the observation-window scan (paper Sec. 3 attention definition, Eq. 3, Eq. 4's alpha per query head):
 //   pass 1  rowstats kernels : stream K, QK^T on the matrix cores, online (max, sum) per window row
 //           lse_kernel       : merge the per-chunk partials into LSE_j
-//   pass 2  colsum kernels   : stream K again, recompute QK^T, exp(z - LSE_j), sum over window rows
-// plus the value-norm ratio rho of Eq. 4 (two small kernels).
+//   pass 2  colsum kernels   : stream K again, recompute QK^T, exp(z - LSE_j), sum over window rows;
+//                              in the fused form also the pooling, head weights and group maximum of
+//                              Eq. 6 (Alg. 1 Stage 3), so that the per-head mass is never written
 //
 // Work decomposition. A "unit" is one (batch, KV head): its G*W window query rows all contract with
-// the same K. Rows are cut into 32-row tiles (one MFMA 32x32 edge), whole heads only; a wave keeps up
-// to four tiles of Q in registers for its lifetime and streams 32-key tiles of K straight from
-// global memory into MFMA operand layout: lane (m, hh) = (lane % 32, lane / 32) owns row m of a tile
-// and the 16-byte chunks 2c+hh of that row. The contraction index may be permuted freely as long as
-// both operands use the same permutation, so whole 16-byte chunks become MFMA k-groups and no LDS
-// transpose is needed. The four waves of a workgroup sweep four adjacent key ranges.
+// the same K. Rows are cut into 32-row tiles (one MFMA 32x32 edge), whole heads only; a wave keeps its
+// tiles of Q (up to eight for bf16, four for f32) in registers for its lifetime and takes 32-key tiles of
+// K in MFMA operand layout: lane (m, hh) = (lane % 32, lane / 32) owns row m of a tile and the 16-byte
+// chunks 2c+hh of that row. The contraction index may be permuted freely as long as both operands use
+// the same permutation, so whole 16-byte chunks become MFMA k-groups and no transpose is needed. The
+// four waves of a workgroup sweep four adjacent key ranges.
 //
 // The two passes use opposite operand orders on purpose:
 //   pass 1: D = K Q^T, lane <-> query row: the running (max, sum) of a row never leaves its lane;

@@ -137,19 +137,15 @@ __device__ __forceinline__ BlockTotals ranked_write(const uint32_t (&key)[NV][4]
                                                     RankScratch<NV> &rs, int tid, int lane, int wave) {
   constexpr int NW = kSelectThreads / kWave;
   int *wave_tot = rs.wave_tot, *pre_gt = rs.pre_gt, *pre_eq = rs.pre_eq;
-  // Ranks in position order: block j, then wave, then lane, then element. Counts travel packed as
-  // (above | equal << 16); a wave covers 256 positions, so neither half overflows.
-  auto own_count = [&](int j) {
-    int c = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) c += (key[j][e] > thr ? 1 : 0) + (key[j][e] == thr ? 0x10000 : 0);
-    return c;
-  };
+  // Ranks in position order: block j, then wave, then lane, then element. A wave's counts come from the
+  // lane masks of the comparisons themselves (population counts on the scalar unit, no cross-lane traffic);
+  // they travel packed as (above | equal << 16): a wave covers 256 positions, so neither half overflows.
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    int c = own_count(j);
+    int c = 0;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+    for (int e = 0; e < 4; ++e)
+      c += __popcll(__ballot(key[j][e] > thr)) + (__popcll(__ballot(key[j][e] == thr)) << 16);
     if (lane == 0) wave_tot[j * NW + wave] = c;
   }
   __syncthreads();
@@ -196,22 +192,22 @@ __device__ __forceinline__ BlockTotals ranked_write(const uint32_t (&key)[NV][4]
   const int tot_gt = pre_gt[NV * NW], tot_eq = pre_eq[NV * NW];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    const int own = own_count(j);
-    int incl = own;
+    // kept keys above / equal in front of this lane's four: the blocks and waves before, then the lower
+    // lanes of this wave (bits of the comparison masks below the lane, counted per element)
+    uint32_t gt_before = (uint32_t)(base_gt + pre_gt[j * NW + wave]);
+    uint32_t eq_before = (uint32_t)(base_eq + pre_eq[j * NW + wave]);
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
+    for (int e = 0; e < 4; ++e) {
+      const unsigned long long mg = __ballot(key[j][e] > thr), me = __ballot(key[j][e] == thr);
+      gt_before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, gt_before));
+      eq_before = __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, eq_before));
     }
-    const int before = incl - own;
-    int gt_before = base_gt + pre_gt[j * NW + wave] + (before & 0xffff);
-    int eq_before = base_eq + pre_eq[j * NW + wave] + (before >> 16);
     const int t = 4 * (j * kSelectThreads + tid);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const bool gt = key[j][e] > thr, eq = key[j][e] == thr;
-      if (gt || (eq && eq_before < need_eq)) {
-        const int pos = gt_before + min(eq_before, need_eq);
+      if (gt || (eq && (int)eq_before < need_eq)) {
+        const int pos = (int)gt_before + min((int)eq_before, need_eq);
         if (pos < kp) out[pos] = t_base + t + e;
       }
       gt_before += gt;
@@ -223,7 +219,7 @@ __device__ __forceinline__ BlockTotals ranked_write(const uint32_t (&key)[NV][4]
 
 template <int NV>
 __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a) {
-  __shared__ int hist[2048];
+  __shared__ int hist[2048 + 1024 + 1024];  // one histogram per digit, all cleared up front
   __shared__ RankScratch<NV> ranks;
   __shared__ uint32_t s_prefix;
   __shared__ int s_k, s_state;  // s_state: 0 = keep all candidates, 1 = select, 2 = keep none
@@ -249,7 +245,7 @@ __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a
     }
   }
 
-  for (int i = tid; i < 2048; i += kSelectThreads) hist[i] = 0;
+  for (int i = tid; i < 4096; i += kSelectThreads) hist[i] = 0;
   __syncthreads();
   digit_histogram<NV, 20, 11, false>(hist, key, 0u, lane);
   __syncthreads();
@@ -275,12 +271,10 @@ __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a
     {
       const uint32_t prefix = s_prefix;
       const int k = s_k;
-      if (tid < 1024) hist[tid] = 0;
-      __syncthreads();
-      digit_histogram<NV, 10, 10, false>(hist, key, prefix, lane);
+      digit_histogram<NV, 10, 10, false>(hist + 2048, key, prefix, lane);
       __syncthreads();
       if (wave == 0) {
-        const BinResult r = find_bin<1024>(hist, k, lane);
+        const BinResult r = find_bin<1024>(hist + 2048, k, lane);
         if (lane == 0) {
           s_prefix = (prefix << 10) | (uint32_t)r.bin;
           s_k = k - r.above;
@@ -291,12 +285,10 @@ __global__ void __launch_bounds__(kSelectThreads) select_reg_kernel(SelectArgs a
     {
       const uint32_t prefix = s_prefix;
       const int k = s_k;
-      if (tid < 1024) hist[tid] = 0;
-      __syncthreads();
-      digit_histogram<NV, 0, 10, false>(hist, key, prefix, lane);
+      digit_histogram<NV, 0, 10, false>(hist + 3072, key, prefix, lane);
       __syncthreads();
       if (wave == 0) {
-        const BinResult r = find_bin<1024>(hist, k, lane);
+        const BinResult r = find_bin<1024>(hist + 3072, k, lane);
         if (lane == 0) {
           s_prefix = (prefix << 10) | (uint32_t)r.bin;
           s_k = k - r.above;
