@@ -28,6 +28,7 @@ struct DecodeArgs {
   float scale2;          // softmax scale * log2(e)
 };
 
+constexpr int kXcds = 8;  // accelerator dies of the part; workgroup i of a launch runs on die i % 8
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / kWave;
 
@@ -73,6 +74,17 @@ __global__ void __launch_bounds__(NW *kWave) decode_partial_kernel(DecodeArgs a)
 
   const int chunk = blockIdx.x;
   int y = blockIdx.y;
+  // One launch over a short KV set: the workgroups that read the same rows (the head chunks of a unit) are
+  // consecutive in y, and consecutive workgroups go to different XCDs, each with an L2 of its own -- the
+  // rows would come from HBM once per head chunk. Within groups of 8 * head_chunks workgroups the index is
+  // transposed, so that a unit's head chunks are 8 apart: same XCD, the second reader hits its L2.
+  if (PIPE && a.head_chunks > 1) {
+    const int span = kXcds * a.head_chunks, base = y / span * span;
+    if (base + span <= (int)gridDim.y) {
+      const int j = y - base;
+      y = base + (j % kXcds) * a.head_chunks + j / kXcds;
+    }
+  }
   const int hc = y % a.head_chunks;
   y /= a.head_chunks;
   const int qi = y % a.n_q, unit = y / a.n_q;
